@@ -1,0 +1,149 @@
+/*
+ * dllmc -- cached bidirectional-transformer denoising step (dLLM-Cache) for MI355X.
+ *
+ * C ABI of libdllmc.so.  All pointers named "device" are HIP device memory owned by the
+ * caller; the library never allocates or frees device memory.  All calls return 0 on
+ * success or a negative DLLMC_E* code; nothing aborts or throws across this boundary.
+ * Work is enqueued on the HIP stream given at creation and the calls do not wait for it:
+ * outputs are valid once the caller has synchronised that stream.
+ *
+ * The method (paper Sec. 3.2): per transformer layer the library keeps K (after RoPE), V,
+ * AttnOut (after the output projection) and FFNOut (after the down projection) for every
+ * token, split into a prompt cache (rows [0, L_p)) and a response cache (rows [L_p, n)).
+ * Step i (counted up from 0) refreshes the prompt features iff i % K_p == 0, refreshes the
+ * whole response iff i % K_r == 0, and otherwise performs the adaptive partial update of
+ * Sec. 3.2.2: project V for all response rows, score each row by the cosine similarity to
+ * its cached V (Eq. cos_sim), overwrite the cached V, and recompute Q/K, attention over all
+ * n cached keys, the output projection and the SwiGLU FFN only for the floor(rho*L_r) rows
+ * with the lowest score (ties: lower index), scattering K, AttnOut and FFNOut back.
+ */
+#ifndef DLLMC_H
+#define DLLMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dllmc_ctx dllmc_ctx; /* opaque host object */
+
+enum { DLLMC_F32 = 0, DLLMC_BF16 = 1 };
+
+enum {
+  DLLMC_OK = 0,
+  DLLMC_EINVAL = -1, /* bad dimension, rho outside [0,1], K_p/K_r < 1, null or misaligned pointer */
+  DLLMC_ESTATE = -2, /* first step is not step 0, or step_idx not increasing */
+  DLLMC_EHIP = -3,   /* a HIP runtime call failed (see dllmc_last_hip_error) */
+  DLLMC_ENOMEM = -4  /* workspace smaller than dllmc_workspace_bytes() */
+};
+
+/* Architecture of the bidirectional transformer (pre-RMSNorm, rotate-half RoPE with pairs
+ * (t, t + head_dim/2), softmax scale 1/sqrt(head_dim), SwiGLU FFN, no biases).  The paper
+ * names only "bidirectional attention" and the three SwiGLU matmuls (complexity appendix);
+ * the rest comes from the LLaDA-8B / Dream-7B shaped workloads. */
+typedef struct {
+  int32_t n_layers;   /* T */
+  int32_t d_model;    /* d */
+  int32_t n_q_heads;  /* H_q */
+  int32_t n_kv_heads; /* H_kv, divides H_q */
+  int32_t head_dim;   /* d_h, even; n_q_heads*head_dim is the attention width d_q */
+  int32_t d_ffn;      /* m */
+  int32_t batch;      /* B independent sequences, each with its own caches and selection */
+  int32_t dtype;      /* DLLMC_F32 or DLLMC_BF16: type of weights, hidden states and caches */
+  float rms_eps;
+  float rope_theta;
+} dllmc_model;
+
+/* One layer's weights: device pointers, borrowed for the life of the context, read-only,
+ * row-major [out, in] (the contraction index is contiguous), element type = model dtype,
+ * 16-byte aligned. */
+typedef struct {
+  const void* attn_norm_g; /* [d]        */
+  const void* wq;          /* [d_q, d]   */
+  const void* wk;          /* [d_kv, d]  */
+  const void* wv;          /* [d_kv, d]  */
+  const void* wo;          /* [d, d_q]   */
+  const void* ffn_norm_g;  /* [d]        */
+  const void* w_gate;      /* [m, d]     */
+  const void* w_up;        /* [m, d]     */
+  const void* w_down;      /* [d, m]     */
+} dllmc_layer_weights;
+
+/* Bytes of device workspace a context needs (caches of Sec. 3.2 plus scratch); 0 if the
+ * arguments are invalid.  Caches take 2*(d_kv + d)*n*B*T elements, the paper's 4*T*d per
+ * token and layer (storage-overhead proof) with d_kv in place of d for grouped KV heads. */
+size_t dllmc_workspace_bytes(const dllmc_model* model, int32_t L_p, int32_t L_r);
+
+/* Create a context.  `layers` is a host array of n_layers entries (copied).  `workspace`
+ * is device memory of at least dllmc_workspace_bytes(), 256-byte aligned, owned by the
+ * caller and used exclusively by this context until dllmc_destroy.  `hip_stream` is a
+ * hipStream_t (NULL = the default stream).  rho in [0,1]; K_p, K_r >= 1 (Sec. 3.2). */
+int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                 int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* floor(rho * L_r): rows recomputed per sequence and layer on an adaptive step (Sec. 3.2.2). */
+int32_t dllmc_num_selected(const dllmc_ctx* ctx);
+
+/* One denoising step (Sec. 3.2 "Iterative Steps").
+ *   hidden_in  device [B, L_p+L_r, d], model dtype: embedded tokens of this step.
+ *   step_idx   0 for the first call (fills both caches), then strictly increasing.
+ *   hidden_out device [B, L_p+L_r, d], model dtype: residual stream after the last layer
+ *              (no final norm).  Prompt rows are the values of the last prompt refresh.
+ *   sel_idx    device [n_layers, B, L_r] int32, may be NULL.  For each layer and sequence the
+ *              first *n_sel entries are the response-row indices (0-based inside the
+ *              response) that were recomputed, ascending; the rest is left untouched.
+ *   n_sel      host out, may be NULL: floor(rho*L_r) on adaptive steps, L_r on refresh steps.
+ * hidden_in and hidden_out may alias. */
+int dllmc_step(dllmc_ctx* ctx, const void* hidden_in, int32_t step_idx, void* hidden_out,
+               int32_t* sel_idx, int32_t* n_sel);
+
+/* Copy one layer's cache tensor to `dst_device`, laid out [B, L_p+L_r, width] in the model
+ * dtype.  which: 0 = K (width d_kv), 1 = V (d_kv), 2 = AttnOut (d), 3 = FFNOut (d). */
+int dllmc_read_cache(dllmc_ctx* ctx, int32_t layer, int32_t which, void* dst_device);
+
+/* Copy the V-verify scores s_j (Eq. cos_sim) of the most recent adaptive step to
+ * `dst_device`, float32 [n_layers, B, L_r]. */
+int dllmc_read_scores(dllmc_ctx* ctx, float* dst_device);
+
+int dllmc_destroy(dllmc_ctx* ctx);
+
+const char* dllmc_strerror(int code);
+/* hipError_t value of the most recent failed HIP call in this process, 0 if none. */
+int dllmc_last_hip_error(void);
+
+/* ---- single operations of the step, exposed for unit parity tests and micro-benchmarks ---- */
+
+/* Bottom-k selection (Sec. 3.2.2): for each of B rows of `scores` (device float32 [B, L]),
+ * write the indices of the k lowest values, ascending by index, to idx_out (device int32
+ * [B, k]); equal values are taken lowest index first.  0 <= k <= L. */
+int dllmc_op_select(const float* scores, int32_t B, int32_t L, int32_t k, int32_t* idx_out,
+                    void* hip_stream);
+
+/* V-verify (Sec. 3.2.2, Eq. cos_sim): V_new = h * Wv^T for `rows` rows, rounded to the model
+ * dtype; scores[r] = cos(V_new[r], v_cache[r]) with the denominator clamped at 1e-8; then
+ * v_cache[r] <- V_new[r].  h: device [rows, d]; wv: [d_kv, d]; v_cache: [rows, d_kv];
+ * scores: float32 [rows]; scratch: device float32 [rows * d_kv * 8]. */
+int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache, float* scores,
+                     int32_t rows, int32_t d, int32_t d_kv, float* scratch, void* hip_stream);
+
+/* Gathered linear map: out[i, :] = a[row_idx[i], :] * w^T in float32, i < M.  a: device
+ * [*, K] model dtype; row_idx: device int32 [M] or NULL for the identity; w: [N, K];
+ * out: float32 [M, N]; scratch: device float32 [M * N * 8]. */
+int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_t M, const void* w,
+                    int32_t N, int32_t K, float* out, float* scratch, void* hip_stream);
+
+/* Bidirectional attention of Mq query rows per sequence over all n cached keys of that
+ * sequence, no mask (complexity appendix: the 4*r^*n*d term).  q, out: device [B, Mq, H_q*d_h];
+ * k_cache, v_cache: device [B, n, H_kv*d_h]; all in the model dtype.  Query head a reads
+ * key/value head a / (H_q/H_kv). */
+int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, const void* k_cache,
+                       const void* v_cache, int32_t n, int32_t H_q, int32_t H_kv, int32_t d_h,
+                       void* out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLLMC_H */

@@ -1,0 +1,223 @@
+"""ctypes binding of libdllmc.so: argument marshalling only.
+
+Every step of the cached denoising path runs inside the HIP library; torch is used
+here for device memory and the stream handle.  Loading fails loudly when the library has
+not been built (``python -c "import __graft_entry__ as g; g.build()"``): there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdllmc.so")
+
+DLLMC_F32, DLLMC_BF16 = 0, 1
+_DTYPES = {"f32": (DLLMC_F32, torch.float32), "bf16": (DLLMC_BF16, torch.bfloat16)}
+_ERR = {-1: "EINVAL", -2: "ESTATE", -3: "EHIP", -4: "ENOMEM"}
+
+EXPORTS = (
+    "dllmc_workspace_bytes", "dllmc_create", "dllmc_num_selected", "dllmc_step",
+    "dllmc_read_cache", "dllmc_read_scores", "dllmc_destroy", "dllmc_strerror",
+    "dllmc_last_hip_error", "dllmc_op_select", "dllmc_op_vverify", "dllmc_op_linear",
+    "dllmc_op_attention",
+)
+
+
+class dllmc_model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
+                ("batch", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float)]
+
+
+class dllmc_layer_weights(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g",
+                                          "w_gate", "w_up", "w_down")]
+
+
+class DllmcError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise DllmcError(f"{LIB_PATH} is missing: build it first (__graft_entry__.build())")
+        L = C.CDLL(LIB_PATH)
+        L.dllmc_workspace_bytes.restype = C.c_size_t
+        L.dllmc_workspace_bytes.argtypes = [C.POINTER(dllmc_model), C.c_int32, C.c_int32]
+        L.dllmc_create.restype = C.c_int
+        L.dllmc_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(dllmc_model),
+                                   C.POINTER(dllmc_layer_weights), C.c_int32, C.c_int32, C.c_float,
+                                   C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.dllmc_num_selected.restype = C.c_int32
+        L.dllmc_num_selected.argtypes = [C.c_void_p]
+        L.dllmc_step.restype = C.c_int
+        L.dllmc_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                 C.POINTER(C.c_int32)]
+        L.dllmc_read_cache.restype = C.c_int
+        L.dllmc_read_cache.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.dllmc_read_scores.restype = C.c_int
+        L.dllmc_read_scores.argtypes = [C.c_void_p, C.c_void_p]
+        L.dllmc_destroy.restype = C.c_int
+        L.dllmc_destroy.argtypes = [C.c_void_p]
+        L.dllmc_strerror.restype = C.c_char_p
+        L.dllmc_strerror.argtypes = [C.c_int]
+        L.dllmc_last_hip_error.restype = C.c_int
+        L.dllmc_op_select.restype = C.c_int
+        L.dllmc_op_select.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_void_p]
+        L.dllmc_op_vverify.restype = C.c_int
+        L.dllmc_op_vverify.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.dllmc_op_linear.restype = C.c_int
+        L.dllmc_op_linear.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dllmc_op_attention.restype = C.c_int
+        L.dllmc_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                         C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_void_p, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        L = lib()
+        msg = L.dllmc_strerror(rc).decode()
+        extra = f" (hipError {L.dllmc_last_hip_error()})" if rc == -3 else ""
+        raise DllmcError(f"{what}: {_ERR.get(rc, rc)} {msg}{extra}")
+
+
+def _stream_handle() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class CachedDenoiser:
+    """dllmc_create / dllmc_step / dllmc_destroy around torch-owned device memory."""
+
+    def __init__(self, *, n_layers: int, d_model: int, n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, d_ffn: int, batch: int, dtype: str,
+                 weights: Sequence[Dict[str, torch.Tensor]], L_p: int, L_r: int, rho: float,
+                 K_p: int, K_r: int, rms_eps: float = 1e-5, rope_theta: float = 10000.0):
+        self._h = None
+        L = lib()
+        code, tdt = _DTYPES[dtype]
+        self.torch_dtype = tdt
+        self.B, self.L_p, self.L_r, self.n, self.d, self.T = batch, L_p, L_r, L_p + L_r, d_model, n_layers
+        self.d_kv = n_kv_heads * head_dim
+        self.model = dllmc_model(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, batch,
+                                 code, rms_eps, rope_theta)
+        if len(weights) != n_layers:
+            raise DllmcError("one weight dict per layer expected")
+        self._weights = weights  # keep the tensors alive: the library borrows the pointers
+        arr = (dllmc_layer_weights * n_layers)()
+        for l, w in enumerate(weights):
+            for name, _ in dllmc_layer_weights._fields_:
+                t = w[name]
+                if not (t.is_cuda and t.is_contiguous() and t.dtype == tdt):
+                    raise DllmcError(f"layer {l} {name}: need a contiguous {tdt} device tensor")
+                setattr(arr[l], name, t.data_ptr())
+        nbytes = L.dllmc_workspace_bytes(C.byref(self.model), L_p, L_r)
+        if nbytes == 0:
+            raise DllmcError("dllmc_workspace_bytes: invalid model description")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.stream = _stream_handle()
+        h = C.c_void_p()
+        _check(L.dllmc_create(C.byref(h), C.byref(self.model), arr, L_p, L_r, rho, K_p, K_r,
+                              self.workspace.data_ptr(), nbytes, self.stream), "dllmc_create")
+        self._h = h
+        self.num_selected = L.dllmc_num_selected(h)
+        self.sel_idx = torch.full((n_layers, batch, L_r), -1, dtype=torch.int32, device="cuda")
+
+    def step(self, hidden_in: torch.Tensor, step_idx: int, hidden_out: Optional[torch.Tensor] = None):
+        """Enqueue one denoising step; returns (hidden_out, n_sel).  self.sel_idx[:, :, :n_sel]
+        holds the recomputed response rows per layer and sequence once the stream is synced."""
+        if hidden_out is None:
+            hidden_out = torch.empty_like(hidden_in)
+        for t in (hidden_in, hidden_out):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype
+                    and tuple(t.shape) == (self.B, self.n, self.d)):
+                raise DllmcError("hidden states must be contiguous [B, n, d] device tensors of the model dtype")
+        n_sel = C.c_int32(0)
+        _check(lib().dllmc_step(self._h, hidden_in.data_ptr(), step_idx, hidden_out.data_ptr(),
+                                self.sel_idx.data_ptr(), C.byref(n_sel)), "dllmc_step")
+        return hidden_out, n_sel.value
+
+    def read_cache(self, layer: int, which: int) -> torch.Tensor:
+        width = self.d_kv if which < 2 else self.d
+        out = torch.empty((self.B, self.n, width), dtype=self.torch_dtype, device="cuda")
+        _check(lib().dllmc_read_cache(self._h, layer, which, out.data_ptr()), "dllmc_read_cache")
+        return out
+
+    def read_scores(self) -> torch.Tensor:
+        out = torch.empty((self.T, self.B, self.L_r), dtype=torch.float32, device="cuda")
+        _check(lib().dllmc_read_scores(self._h, out.data_ptr()), "dllmc_read_scores")
+        return out
+
+    def close(self) -> None:
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib().dllmc_destroy(h), "dllmc_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def op_select(scores: torch.Tensor, k: int) -> torch.Tensor:
+    B, Lr = scores.shape
+    out = torch.empty((B, max(k, 1)), dtype=torch.int32, device="cuda")
+    _check(lib().dllmc_op_select(scores.data_ptr(), B, Lr, k, out.data_ptr(), _stream_handle()),
+           "dllmc_op_select")
+    return out[:, :k]
+
+
+def op_vverify(dtype: str, h: torch.Tensor, wv: torch.Tensor, v_cache: torch.Tensor) -> torch.Tensor:
+    """Scores [rows]; v_cache is overwritten with the new V rows."""
+    rows, d = h.shape
+    d_kv = wv.shape[0]
+    scores = torch.empty(rows, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(rows * d_kv * 8, dtype=torch.float32, device="cuda")
+    _check(lib().dllmc_op_vverify(_DTYPES[dtype][0], h.data_ptr(), wv.data_ptr(), v_cache.data_ptr(),
+                                  scores.data_ptr(), rows, d, d_kv, scratch.data_ptr(),
+                                  _stream_handle()), "dllmc_op_vverify")
+    return scores
+
+
+def op_linear(dtype: str, a: torch.Tensor, w: torch.Tensor, row_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    K = a.shape[1]
+    N = w.shape[0]
+    M = a.shape[0] if row_idx is None else row_idx.numel()
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    scratch = torch.empty(M * N * 8, dtype=torch.float32, device="cuda")
+    _check(lib().dllmc_op_linear(_DTYPES[dtype][0], a.data_ptr(), _ptr(row_idx), M, w.data_ptr(), N, K,
+                                 out.data_ptr(), scratch.data_ptr(), _stream_handle()),
+           "dllmc_op_linear")
+    return out
+
+
+def op_attention(dtype: str, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                 H_q: int, H_kv: int, d_h: int) -> torch.Tensor:
+    B, Mq, _ = q.shape
+    n = k_cache.shape[1]
+    out = torch.empty_like(q)
+    _check(lib().dllmc_op_attention(_DTYPES[dtype][0], q.data_ptr(), B, Mq, k_cache.data_ptr(),
+                                    v_cache.data_ptr(), n, H_q, H_kv, d_h, out.data_ptr(),
+                                    _stream_handle()), "dllmc_op_attention")
+    return out

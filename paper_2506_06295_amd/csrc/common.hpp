@@ -1,0 +1,152 @@
+// Shared device helpers and the host-side launch interface of the dllmc kernels (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dllmc {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// ---- storage types -------------------------------------------------------------------
+// bf16 values are handled as raw 16-bit patterns; conversion is round-to-nearest-even.
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) {
+  return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<bf16_t>(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float ldf(const T* p);
+template <> __device__ __forceinline__ float ldf<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ldf<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void stf(T* p, float v);
+template <> __device__ __forceinline__ void stf<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void stf<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// value after a round trip through the storage type
+template <typename T> __device__ __forceinline__ float roundf_to(float v);
+template <> __device__ __forceinline__ float roundf_to<float>(float v) { return v; }
+template <> __device__ __forceinline__ float roundf_to<bf16_t>(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+
+// ---- wavefront / workgroup reductions ------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+// Sum over a workgroup of NW wavefronts; `red` is NW floats of LDS.  Every thread gets the
+// total, summed in wave order (deterministic).
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) t += red[i];
+  return t;
+}
+
+// ---- host-side launchers (defined in the kernels_*.hip files) --------------------------
+// dtype: 0 = float32 storage, 1 = bf16 storage.  All pointers are device pointers.
+
+// C_part[s][i][:] (float32, s < S) = partial products of A[rows[i], :] * [W0; W1]^T over the
+// s-th slice of the contraction index.  W0 holds output columns [0, N0), W1 columns [N0, N)
+// (W1 may be null when N0 == N).  rows == nullptr means the identity.  Returns the number
+// of slices S it used (>= 1) so that consumers sum c_part[0..S) in order; c_part must hold
+// gemm_max_slices() * M * N floats.
+int gemm_max_slices();
+int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
+                const void* W1, int N0, int N, int K, float* c_part, hipStream_t st);
+
+// out[i][:] = sum_s c_part[s][i][:]
+void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, hipStream_t st);
+
+struct RowKernelArgs {
+  int dtype;
+  int n;            // rows per sequence (L_p + L_r)
+  int L_p;
+  int d;            // model width
+  float eps;
+};
+
+// x[row] = hidden_in[row]; h[row] = T(rmsnorm(x[row]) * g) for row in rows[0..M)
+void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int* rows, int M,
+                       const void* gain, float* x, void* h, hipStream_t st);
+
+// V finalize: for i < M: row = rows[i] (i if rows == nullptr); v = T(sum_s c_part[s][i][:]);
+// if score != nullptr and row is a response row: score[seq][j] = cos(v, v_cache[row]);
+// v_cache[row] = v.
+void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
+                       int d_kv, void* v_cache, float* score, hipStream_t st);
+
+// Q/K finalize: for i < M: row = rows[i], pos = row % n; c = sum_s c_part[s][i][0..d_q+d_kv);
+// q_out[i] = T(rope(c[0..d_q))), k_cache[row] = T(rope(c[d_q..))).  rope_tab[pos][t] =
+// (cos, sin) of pos * theta^(-2t/d_h).
+void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
+                        int d_q, int d_kv, int d_h, const float2* rope_tab, void* q_out,
+                        void* k_cache, hipStream_t st);
+
+// Output-projection finalize over the carried rows: for i < Mc: row = carried[i]; ci = inv[row];
+// if ci >= 0: attn_cache[row] = T(sum_s c_part[s][ci][:]) (c_part slices hold M_R rows);
+// x[row] += attn_cache[row]; if ci >= 0: g_out[ci] = T(rmsnorm(x[row]) * gain).
+void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
+                       const int* carried, int Mc, const int* inv, void* attn_cache, float* x,
+                       const void* gain, void* g_out, hipStream_t st);
+
+// SwiGLU: u[i][j] = T(silu(c[i][j]) * c[i][m + j]) with c = sum_s c_part[s] of width 2m.
+void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st);
+
+// Down-projection finalize over the carried rows: ffn_cache update like launch_o_finalize;
+// x[row] += ffn_cache[row]; then either h[row] = T(rmsnorm(x[row]) * next_gain) (next_gain
+// != nullptr) or, for the last layer, hidden_out[row] = T(x[row]) and, for prompt rows when
+// prompt_out != nullptr, prompt_out[seq][row % n] = T(x[row]).
+void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
+                          const int* carried, int Mc, const int* inv, void* ffn_cache, float* x,
+                          const void* next_gain, void* h, void* hidden_out, void* prompt_out,
+                          hipStream_t st);
+
+// hidden_out[b][t] = prompt_out[b][t] for all prompt rows
+void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, void* hidden_out,
+                        hipStream_t st);
+
+// Bottom-k selection per sequence.  scores: [B, L] float32.  Writes, for sequence b and the
+// pos-th selected index j (ascending):
+//   sel_out[b*sel_stride + pos] = j                          (if sel_out != nullptr)
+//   rows_out[b*per_seq + off + pos] = b*n + L_p + j          (if rows_out != nullptr)
+//   inv_out[b*n + L_p + j] = b*per_seq + off + pos, and -1 for rows not selected
+void launch_select(const float* scores, int B, int L, int k, int* sel_out, int sel_stride,
+                   int* rows_out, int per_seq, int off, int* inv_out, int n, int L_p,
+                   hipStream_t st);
+
+// Attention of Mq compact queries per sequence over all n keys of that sequence.
+// q, out: [B, Mq, H_q*d_h]; k_cache, v_cache: [B, n, H_kv*d_h].
+// The float32 / odd-head-width kernel keeps one row of n scores in LDS.
+bool attention_supported(int dtype, int d_h, int n);
+void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cache,
+                      const void* v_cache, int n, int H_q, int H_kv, int d_h, void* out,
+                      hipStream_t st);
+
+// Row lists: for b < B, t < count: ci = b*per_seq + off + t, row = b*n + first + t;
+// rows[ci] = row (if rows), inv[row] = ci (if inv).
+void launch_iota_rows(int* rows, int* inv, int B, int n, int first, int count, int per_seq,
+                      int off, hipStream_t st);
+void launch_fill_i32(int* p, int value, size_t count, hipStream_t st);
+// sel[r][j] = j for r < rows, j < L_r
+void launch_fill_sel_identity(int* sel, int rows, int L_r, hipStream_t st);
+
+}  // namespace dllmc

@@ -1,0 +1,362 @@
+// Host side of libdllmc.so: the C ABI, the context (workspace carving, cache schedule of
+// paper Sec. 3.2) and the per-layer launch sequence of one denoising step.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/dllmc.h"
+#include "common.hpp"
+
+using namespace dllmc;
+
+namespace {
+
+int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return DLLMC_EHIP;
+}
+#define HIP_TRY(expr)                             \
+  do {                                            \
+    hipError_t e__ = (expr);                      \
+    if (e__ != hipSuccess) return hip_fail(e__);  \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool model_ok(const dllmc_model* m, int L_p, int L_r) {
+  if (!m) return false;
+  if (m->n_layers < 1 || m->d_model < 1 || m->n_q_heads < 1 || m->n_kv_heads < 1 ||
+      m->head_dim < 2 || m->d_ffn < 1 || m->batch < 1)
+    return false;
+  if (m->head_dim % 2 || m->n_q_heads % m->n_kv_heads) return false;
+  if (m->dtype != DLLMC_F32 && m->dtype != DLLMC_BF16) return false;
+  if (!(m->rms_eps >= 0.f) || !(m->rope_theta > 0.f)) return false;
+  if (L_p < 0 || L_r < 1) return false;
+  const long long rows = static_cast<long long>(m->batch) * (static_cast<long long>(L_p) + L_r);
+  if (rows > (1ll << 24)) return false;  // row ids and compact indices are int32 with headroom
+  if (!attention_supported(m->dtype, m->head_dim, L_p + L_r)) return false;
+  return true;
+}
+
+// Carving of the caller's workspace.  Every region starts 256-byte aligned.
+struct Layout {
+  size_t esz;
+  size_t cache_k, cache_v, cache_ao, cache_fo;  // per-layer strides inside their regions
+  size_t off_k, off_v, off_ao, off_fo, off_prompt_out, off_x, off_h, off_q, off_a, off_g, off_u,
+      off_cws, off_scores, off_carried, off_rows, off_inv, off_rope, total;
+};
+
+Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
+  Layout L{};
+  const size_t esz = m.dtype == DLLMC_BF16 ? 2 : 4;
+  const size_t B = m.batch, n = static_cast<size_t>(L_p) + L_r, T = m.n_layers;
+  const size_t d = m.d_model, d_q = static_cast<size_t>(m.n_q_heads) * m.head_dim,
+               d_kv = static_cast<size_t>(m.n_kv_heads) * m.head_dim, mf = m.d_ffn;
+  const size_t rows = B * n;
+  L.esz = esz;
+  L.cache_k = L.cache_v = align_up(rows * d_kv * esz, 256);
+  L.cache_ao = L.cache_fo = align_up(rows * d * esz, 256);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o += align_up(bytes, 256); return r; };
+  L.off_k = take(L.cache_k * T);
+  L.off_v = take(L.cache_v * T);
+  L.off_ao = take(L.cache_ao * T);
+  L.off_fo = take(L.cache_fo * T);
+  L.off_prompt_out = take(B * L_p * d * esz);
+  L.off_x = take(rows * d * sizeof(float));
+  L.off_h = take(rows * d * esz);
+  L.off_q = take(rows * d_q * esz);
+  L.off_a = take(rows * d_q * esz);
+  L.off_g = take(rows * d * esz);
+  L.off_u = take(rows * mf * esz);
+  size_t n_max = 2 * mf;
+  if (d_q + d_kv > n_max) n_max = d_q + d_kv;
+  if (d > n_max) n_max = d;
+  // GEMM output slices: S*tiles < 512 + tiles workgroup tiles of 64 x 128 floats
+  const size_t cws_floats = align_up(rows, 64) * n_max + static_cast<size_t>(640) * 64 * 128;
+  L.off_cws = take(cws_floats * sizeof(float));
+  L.off_scores = take(T * B * L_r * sizeof(float));
+  L.off_carried = take(rows * sizeof(int));
+  L.off_rows = take(rows * sizeof(int));
+  L.off_inv = take(rows * sizeof(int));
+  L.off_rope = take(n * (m.head_dim / 2) * sizeof(float2));
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+struct dllmc_ctx {
+  dllmc_model m;
+  std::vector<dllmc_layer_weights> layers;
+  int L_p, L_r, n, k_sel, K_p, K_r;
+  float rho;
+  hipStream_t st;
+  int last_step;
+  Layout lay;
+  char* ws;
+  bool have_scores;
+
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+  void* cache(int which, int layer) const {
+    switch (which) {
+      case 0: return ws + lay.off_k + lay.cache_k * layer;
+      case 1: return ws + lay.off_v + lay.cache_v * layer;
+      case 2: return ws + lay.off_ao + lay.cache_ao * layer;
+      default: return ws + lay.off_fo + lay.cache_fo * layer;
+    }
+  }
+};
+
+extern "C" {
+
+size_t dllmc_workspace_bytes(const dllmc_model* model, int32_t L_p, int32_t L_r) {
+  if (!model_ok(model, L_p, L_r)) return 0;
+  return make_layout(*model, L_p, L_r).total;
+}
+
+int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                 int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (!out) return DLLMC_EINVAL;
+  *out = nullptr;
+  if (!model_ok(model, L_p, L_r) || !layers || !workspace) return DLLMC_EINVAL;
+  if (!(rho >= 0.f && rho <= 1.f) || K_p < 1 || K_r < 1) return DLLMC_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return DLLMC_EINVAL;
+  for (int l = 0; l < model->n_layers; ++l) {
+    const void* ps[9] = {layers[l].attn_norm_g, layers[l].wq, layers[l].wk, layers[l].wv,
+                         layers[l].wo, layers[l].ffn_norm_g, layers[l].w_gate, layers[l].w_up,
+                         layers[l].w_down};
+    for (const void* p : ps)
+      if (!p || (reinterpret_cast<uintptr_t>(p) & 15u)) return DLLMC_EINVAL;
+  }
+  const Layout lay = make_layout(*model, L_p, L_r);
+  if (workspace_bytes < lay.total) return DLLMC_ENOMEM;
+
+  dllmc_ctx* c = new (std::nothrow) dllmc_ctx();
+  if (!c) return DLLMC_ENOMEM;
+  c->m = *model;
+  c->layers.assign(layers, layers + model->n_layers);
+  c->L_p = L_p;
+  c->L_r = L_r;
+  c->n = L_p + L_r;
+  c->rho = rho;
+  c->K_p = K_p;
+  c->K_r = K_r;
+  // floor(rho * |y|), |y| = response length (Sec. 3.2.2)
+  c->k_sel = static_cast<int>(std::floor(static_cast<double>(rho) * L_r + 1e-6));
+  if (c->k_sel > L_r) c->k_sel = L_r;
+  c->st = static_cast<hipStream_t>(hip_stream);
+  c->last_step = -1;
+  c->lay = lay;
+  c->ws = static_cast<char*>(workspace);
+  c->have_scores = false;
+
+  // RoPE table in double on the host: (cos, sin)(pos * theta^(-2t/d_h))
+  const int half = model->head_dim / 2;
+  std::vector<float2> tab(static_cast<size_t>(c->n) * half);
+  for (int pos = 0; pos < c->n; ++pos)
+    for (int t = 0; t < half; ++t) {
+      const double w = std::pow(static_cast<double>(model->rope_theta),
+                                -2.0 * t / static_cast<double>(model->head_dim));
+      const double ang = pos * w;
+      tab[static_cast<size_t>(pos) * half + t] =
+          make_float2(static_cast<float>(std::cos(ang)), static_cast<float>(std::sin(ang)));
+    }
+  hipError_t e = hipMemcpyAsync(c->ws + lay.off_rope, tab.data(), tab.size() * sizeof(float2),
+                                hipMemcpyHostToDevice, c->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->st);
+  if (e != hipSuccess) {
+    delete c;
+    return hip_fail(e);
+  }
+  *out = c;
+  return DLLMC_OK;
+}
+
+int32_t dllmc_num_selected(const dllmc_ctx* ctx) { return ctx ? ctx->k_sel : DLLMC_EINVAL; }
+
+int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidden_out,
+               int32_t* sel_idx, int32_t* n_sel) {
+  if (!c || !hidden_in || !hidden_out || step_idx < 0) return DLLMC_EINVAL;
+  if ((c->last_step < 0 && step_idx != 0) || step_idx <= c->last_step) return DLLMC_ESTATE;
+  (void)hipGetLastError();  // do not inherit a stale error
+
+  const dllmc_model& m = c->m;
+  const int B = m.batch, n = c->n, L_p = c->L_p, L_r = c->L_r, T = m.n_layers;
+  const int d = m.d_model, d_h = m.head_dim, d_q = m.n_q_heads * d_h, d_kv = m.n_kv_heads * d_h;
+  const int mf = m.d_ffn, dt = m.dtype;
+  hipStream_t st = c->st;
+
+  // Sec. 3.2 "Iterative Steps": which caches are refreshed at this step
+  const bool P = (step_idx % c->K_p == 0) && L_p > 0;
+  const bool Rf = (step_idx % c->K_r == 0);
+  const int carried_per_seq = (P ? L_p : 0) + L_r;
+  const int Mc = B * carried_per_seq;
+  const int sel_per_seq = Rf ? L_r : c->k_sel;
+  const int per_seq = (P ? L_p : 0) + sel_per_seq;  // recomputed rows per sequence
+  const int M_R = B * per_seq;
+  const int sel_off = P ? L_p : 0;
+  if (n_sel) *n_sel = sel_per_seq;
+
+  const RowKernelArgs ra{dt, n, L_p, d, m.rms_eps};
+  int* carried = c->at<int>(c->lay.off_carried);
+  int* rows_R = c->at<int>(c->lay.off_rows);
+  int* inv = c->at<int>(c->lay.off_inv);
+  float* x = c->at<float>(c->lay.off_x);
+  void* h = c->ws + c->lay.off_h;
+  void* qbuf = c->ws + c->lay.off_q;
+  void* abuf = c->ws + c->lay.off_a;
+  void* gbuf = c->ws + c->lay.off_g;
+  void* ubuf = c->ws + c->lay.off_u;
+  float* cws = c->at<float>(c->lay.off_cws);
+  float* scores = c->at<float>(c->lay.off_scores);
+  void* prompt_out = c->ws + c->lay.off_prompt_out;
+  const float2* rope_tab = c->at<float2>(c->lay.off_rope);
+
+  // row lists of this step
+  launch_iota_rows(carried, nullptr, B, n, P ? 0 : L_p, carried_per_seq, carried_per_seq, 0, st);
+  if (P) launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq, 0, st);
+  if (Rf) {
+    launch_iota_rows(rows_R, inv, B, n, L_p, L_r, per_seq, sel_off, st);
+    if (sel_idx) launch_fill_sel_identity(sel_idx, T * B, L_r, st);
+  }
+
+  launch_embed_norm(ra, hidden_in, carried, Mc, c->layers[0].attn_norm_g, x, h, st);
+
+  for (int l = 0; l < T; ++l) {
+    const dllmc_layer_weights& w = c->layers[l];
+    void* Kc = c->cache(0, l);
+    void* Vc = c->cache(1, l);
+    // V-verify: V for every carried row, score against the cache, overwrite the cache
+    int S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, st);
+    float* sc = scores + static_cast<size_t>(l) * B * L_r;
+    launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, Rf ? nullptr : sc, st);
+    if (!Rf)
+      launch_select(sc, B, L_r, c->k_sel,
+                    sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
+                    per_seq, sel_off, inv, n, L_p, st);
+    S = 1;
+    if (M_R > 0) {
+      S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, st);
+      launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, Kc, st);
+      launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf, st);
+      S = launch_gemm(dt, abuf, d_q, nullptr, M_R, w.wo, nullptr, d, d, d_q, cws, st);
+    }
+    launch_o_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
+    if (M_R > 0) {
+      S = launch_gemm(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, 2 * mf, d, cws, st);
+      launch_swiglu(dt, cws, S, M_R, mf, ubuf, st);
+      S = launch_gemm(dt, ubuf, mf, nullptr, M_R, w.w_down, nullptr, d, d, mf, cws, st);
+    }
+    const bool last = (l == T - 1);
+    launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(3, l), x,
+                         last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
+                         (last && P) ? prompt_out : nullptr, st);
+  }
+  if (!P) launch_copy_prompt(ra, B, prompt_out, hidden_out, st);
+
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  if (!Rf) c->have_scores = true;
+  c->last_step = step_idx;
+  return DLLMC_OK;
+}
+
+int dllmc_read_cache(dllmc_ctx* c, int32_t layer, int32_t which, void* dst_device) {
+  if (!c || !dst_device || layer < 0 || layer >= c->m.n_layers || which < 0 || which > 3)
+    return DLLMC_EINVAL;
+  const size_t width = which < 2 ? static_cast<size_t>(c->m.n_kv_heads) * c->m.head_dim
+                                 : static_cast<size_t>(c->m.d_model);
+  const size_t bytes = static_cast<size_t>(c->m.batch) * c->n * width * c->lay.esz;
+  HIP_TRY(hipMemcpyAsync(dst_device, c->cache(which, layer), bytes, hipMemcpyDeviceToDevice, c->st));
+  return DLLMC_OK;
+}
+
+int dllmc_read_scores(dllmc_ctx* c, float* dst_device) {
+  if (!c || !dst_device) return DLLMC_EINVAL;
+  if (!c->have_scores) return DLLMC_ESTATE;
+  const size_t bytes = static_cast<size_t>(c->m.n_layers) * c->m.batch * c->L_r * sizeof(float);
+  HIP_TRY(hipMemcpyAsync(dst_device, c->ws + c->lay.off_scores, bytes, hipMemcpyDeviceToDevice,
+                         c->st));
+  return DLLMC_OK;
+}
+
+int dllmc_destroy(dllmc_ctx* c) {
+  if (!c) return DLLMC_EINVAL;
+  hipError_t e = hipStreamSynchronize(c->st);  // the workspace goes back to the caller idle
+  delete c;
+  if (e != hipSuccess) return hip_fail(e);
+  return DLLMC_OK;
+}
+
+const char* dllmc_strerror(int code) {
+  switch (code) {
+    case DLLMC_OK: return "ok";
+    case DLLMC_EINVAL: return "invalid argument";
+    case DLLMC_ESTATE: return "call out of order (step 0 first, then increasing step_idx)";
+    case DLLMC_EHIP: return "HIP runtime error";
+    case DLLMC_ENOMEM: return "workspace too small";
+    default: return "unknown error";
+  }
+}
+
+int dllmc_last_hip_error(void) { return g_last_hip_error; }
+
+// ---- single operations ------------------------------------------------------------------
+
+int dllmc_op_select(const float* scores, int32_t B, int32_t L, int32_t k, int32_t* idx_out,
+                    void* hip_stream) {
+  if (!scores || B < 1 || L < 1 || k < 0 || k > L || (k > 0 && !idx_out)) return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  launch_select(scores, B, L, k, idx_out, k, nullptr, 0, 0, nullptr, L, 0,
+                static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache, float* scores,
+                     int32_t rows, int32_t d, int32_t d_kv, float* scratch, void* hip_stream) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !h || !wv || !v_cache || !scores || !scratch ||
+      rows < 1 || d < 1 || d_kv < 1)
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int S = launch_gemm(dtype, h, d, nullptr, rows, wv, nullptr, d_kv, d_kv, d, scratch, st);
+  const RowKernelArgs ra{dtype, rows, 0, d, 0.f};
+  launch_v_finalize(ra, scratch, S, nullptr, rows, d_kv, v_cache, scores, st);
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_t M, const void* w,
+                    int32_t N, int32_t K, float* out, float* scratch, void* hip_stream) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !a || !w || !out || !scratch || M < 1 ||
+      N < 1 || K < 1)
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int S = launch_gemm(dtype, a, K, row_idx, M, w, nullptr, N, N, K, scratch, st);
+  launch_reduce_slices(scratch, S, M, N, out, st);
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, const void* k_cache,
+                       const void* v_cache, int32_t n, int32_t H_q, int32_t H_kv, int32_t d_h,
+                       void* out, void* hip_stream) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !q || !k_cache || !v_cache || !out || B < 1 ||
+      Mq < 1 || n < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv || d_h < 1 ||
+      !attention_supported(dtype, d_h, n))
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  launch_attention(dtype, q, B, Mq, k_cache, v_cache, n, H_q, H_kv, d_h, out,
+                   static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+}  // extern "C"

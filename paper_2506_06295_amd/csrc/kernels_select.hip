@@ -1,0 +1,121 @@
+// Bottom-k selection of the V-verify scores (paper Sec. 3.2.2): per sequence, the k rows with
+// the lowest score, equal scores lowest index first, emitted ascending by index.
+//
+// One workgroup per sequence.  Scores are mapped to unsigned keys whose integer order is the
+// float order; four 8-bit radix passes over an LDS histogram find the key of the k-th
+// smallest element and how many elements equal to it still belong to the set; one ordered
+// compaction pass (ballot + popcount prefix sums per wavefront, LDS across wavefronts) then
+// writes the indices in ascending order.  Everything is integer work after the key mapping,
+// so the result is exact and independent of scheduling.
+#include "common.hpp"
+
+namespace dllmc {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kNW = kThreads / kWave;
+
+__device__ __forceinline__ uint32_t order_key(float s) {
+  s += 0.0f;  // -0.0 -> +0.0 so that the two zeros tie
+  const uint32_t u = __float_as_uint(s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Exclusive prefix sum of v over the workgroup in thread order; total in *total.
+// scratch: kNW + 1 uints of LDS.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const uint32_t t = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) scratch[w] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kNW; ++i) {
+    const uint32_t s = scratch[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ scores, int L, int k,
+                                                     int* __restrict__ sel_out, int sel_stride,
+                                                     int* __restrict__ rows_out, int per_seq,
+                                                     int off, int* __restrict__ inv_out, int n,
+                                                     int L_p) {
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t scan_scratch[kNW + 1];
+  __shared__ uint32_t sh_prefix, sh_need;
+  const int b = blockIdx.x;
+  const float* s = scores + static_cast<size_t>(b) * L;
+
+  uint32_t kth = 0, need = 0;
+  if (k > 0) {
+    uint32_t prefix = 0;
+    need = static_cast<uint32_t>(k);
+    for (int pass = 3; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      const uint32_t himask = pass == 3 ? 0u : (0xFFFFFFFFu << (shift + 8));
+      hist[threadIdx.x] = 0;
+      __syncthreads();
+      for (int j = threadIdx.x; j < L; j += kThreads) {
+        const uint32_t key = order_key(s[j]);
+        if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      uint32_t total;
+      const uint32_t cnt = hist[threadIdx.x];
+      const uint32_t excl = block_excl_scan(cnt, scan_scratch, &total);
+      // exactly one bucket satisfies excl < need <= excl + cnt
+      if (excl < need && need <= excl + cnt) {
+        sh_prefix = prefix | (static_cast<uint32_t>(threadIdx.x) << shift);
+        sh_need = need - excl;
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      need = sh_need;
+      __syncthreads();
+    }
+    kth = prefix;
+  }
+
+  uint32_t base_sel = 0, base_eq = 0;
+  for (int j0 = 0; j0 < L; j0 += kThreads) {
+    const int j = j0 + threadIdx.x;
+    const bool valid = j < L;
+    const uint32_t key = valid ? order_key(s[j]) : 0xFFFFFFFFu;
+    const bool less = valid && k > 0 && key < kth;
+    const bool eq = valid && k > 0 && key == kth;
+    uint32_t tot_eq, tot_take;
+    const uint32_t eq_rank = base_eq + block_excl_scan(eq ? 1u : 0u, scan_scratch, &tot_eq);
+    const bool take = less || (eq && eq_rank < need);
+    const uint32_t pos = base_sel + block_excl_scan(take ? 1u : 0u, scan_scratch, &tot_take);
+    if (take) {
+      if (sel_out) sel_out[static_cast<size_t>(b) * sel_stride + pos] = j;
+      if (rows_out) rows_out[b * per_seq + off + static_cast<int>(pos)] = b * n + L_p + j;
+    }
+    if (valid && inv_out) inv_out[b * n + L_p + j] = take ? b * per_seq + off + static_cast<int>(pos) : -1;
+    base_eq += tot_eq;
+    base_sel += tot_take;
+  }
+}
+
+}  // namespace
+
+void launch_select(const float* scores, int B, int L, int k, int* sel_out, int sel_stride,
+                   int* rows_out, int per_seq, int off, int* inv_out, int n, int L_p,
+                   hipStream_t st) {
+  if (B <= 0 || L <= 0) return;
+  hipLaunchKernelGGL(k_select, dim3(B), dim3(kThreads), 0, st, scores, L, k, sel_out, sel_stride,
+                     rows_out, per_seq, off, inv_out, n, L_p);
+}
+
+}  // namespace dllmc
