@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the cached denoising step (dLLM-Cache) on one MI355X.
+
+A "step" is one denoising step: one pass of the whole hot path (all layers: V-verify,
+selection, partial recompute, cache scatter) over the batch.  Steps follow the workload's
+schedule (step index i mod the schedule length), so --steps equal to the schedule length times
+one whole generation with its mix of full-refresh, response-refresh and adaptive steps.
+Inputs (embedded tokens of every schedule step) and weights are resident in HBM before the
+timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def make_denoiser(binding, cfg, weights, **over):
+    return binding.CachedDenoiser(
+        n_layers=cfg.T, d_model=cfg.d, n_q_heads=cfg.H_q, n_kv_heads=cfg.H_kv, head_dim=cfg.d_h,
+        d_ffn=cfg.m, batch=cfg.B, dtype=cfg.dtype, weights=weights, L_p=cfg.L_p, L_r=cfg.L_r,
+        rho=over.get("rho", cfg.rho), K_p=over.get("K_p", cfg.K_p), K_r=over.get("K_r", cfg.K_r),
+        rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+
+
+def step_kind(cfg, i):
+    P, R = i % cfg.K_p == 0, i % cfg.K_r == 0
+    return "full" if P and R else "prompt+adaptive" if P else "response" if R else "adaptive"
+
+
+def cpu_baseline(cfg, dev_weights, hidden_host, sample_layers=2):
+    """The CPU oracle timed on the host cores: one step of each kind on `sample_layers` layers,
+    scaled to the full depth and to the schedule's kind counts."""
+    import numpy as np
+    from oracle import dllm_cache_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ls = min(sample_layers, cfg.T)
+    ws = [{k: v.float().cpu().numpy().astype(np.float64) for k, v in dev_weights[l].items()}
+          for l in range(Ls)]
+    model = O.Model(Ls, cfg.d, cfg.H_q, cfg.H_kv, cfg.d_h, cfg.m, cfg.rms_eps, cfg.rope_theta)
+    # K_p = 3, K_r = 2 visits the four step kinds in steps 0..3
+    ora = O.CachedDenoiser(model, ws, cfg.B, cfg.L_p, cfg.L_r, cfg.rho, 3, 2,
+                           storage="bf16" if cfg.dtype == "bf16" else "f64")
+    kinds = ["full", "adaptive", "response", "prompt+adaptive"]
+    t_kind = {}
+    for i, kind in enumerate(kinds):
+        t0 = time.perf_counter()
+        ora.step(hidden_host[i % len(hidden_host)].astype(np.float64), i)
+        t_kind[kind] = time.perf_counter() - t0
+    counts = {k: 0 for k in kinds}
+    for i in range(cfg.steps):
+        counts[step_kind(cfg, i)] += 1
+    sched_s = sum(counts[k] * t_kind[k] for k in kinds) * (cfg.T / Ls)
+    return {
+        "value": cfg.steps / sched_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"numpy float64 oracle, {Ls} of {cfg.T} layers, one step of each kind "
+                   f"(full/adaptive/response/prompt+adaptive = "
+                   f"{t_kind['full']:.2f}/{t_kind['adaptive']:.2f}/{t_kind['response']:.2f}/"
+                   f"{t_kind['prompt+adaptive']:.2f} s), scaled by {cfg.T // Ls}x depth and the "
+                   f"schedule's kind counts {counts}"),
+        "response_tokens_per_s": cfg.B * cfg.L_r / sched_s,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: one schedule)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default: one schedule)")
+    ap.add_argument("--config", default="llada8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-uncached", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences would shard across GPUs "
+              "with no exchange step; not built). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_06295_amd import binding, inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    cfg = I.CONFIGS[args.config]
+    K = args.steps if args.steps is not None else cfg.steps
+    W = args.warmup if args.warmup is not None else cfg.steps
+
+    weights = I.device_weights(cfg)
+    sched = I.TokenSchedule(cfg)
+    hidden_host = [sched.hidden_in(i) for i in range(cfg.steps)]
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    hidden = [torch.from_numpy(h).cuda().to(tdt).contiguous() for h in hidden_host]
+    out = torch.empty_like(hidden[0])
+    den = make_denoiser(binding, cfg, weights)
+
+    def run(count, start=0):
+        for s in range(start, start + count):
+            i = s % cfg.steps
+            den.step(hidden[i], i, out)
+
+    # warm-up, then the timed region: exactly K steps between two device synchronisations
+    w_aligned = W
+    run(w_aligned)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K, start=w_aligned)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    steps_per_s = K / elapsed
+    kinds_timed = {}
+    for s in range(w_aligned, w_aligned + K):
+        kinds_timed[step_kind(cfg, s % cfg.steps)] = kinds_timed.get(step_kind(cfg, s % cfg.steps), 0) + 1
+
+    result = {
+        "metric": "cached denoise steps/s",
+        "value": steps_per_s,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": 1e3 * elapsed / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} heads={cfg.H_q}/{cfg.H_kv}x{cfg.d_h} "
+                               f"m={cfg.m} B={cfg.B} L_p={cfg.L_p} L_r={cfg.L_r} rho={cfg.rho} "
+                               f"K_p={cfg.K_p} K_r={cfg.K_r} schedule={cfg.steps} steps",
+                   "step_kinds_timed": kinds_timed, "seed": cfg.seed},
+        "response_tokens_per_s": cfg.B * cfg.L_r * steps_per_s / cfg.steps,
+        "token_rows_per_s": cfg.B * cfg.L_r * steps_per_s,
+    }
+
+    # per-kernel pass over the same K steps with HIP events around every launch
+    if not args.no_profile:
+        den.profile_enable(True)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+        for j, s in enumerate(range(w_aligned, w_aligned + K)):
+            i = s % cfg.steps
+            ev[j][0].record()
+            den.step(hidden[i], i, out)
+            ev[j][1].record()
+        stats = den.profile_read(reset=True)
+        den.profile_enable(False)
+        per_kind = {}
+        for j, s in enumerate(range(w_aligned, w_aligned + K)):
+            per_kind.setdefault(step_kind(cfg, s % cfg.steps), []).append(ev[j][0].elapsed_time(ev[j][1]))
+        result["ms_per_step_kind"] = {k: float(np.median(v)) for k, v in per_kind.items()}
+        gemm = [stats[k] for k in ("gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down")]
+        g_ms = sum(g["ms"] for g in gemm)
+        g_bytes = sum(g["alg_bytes"] for g in gemm)
+        g_flops = sum(g["flops"] for g in gemm)
+        g_n = sum(g["launches"] for g in gemm)
+        total_ms = sum(v["ms"] for v in stats.values())
+        achieved = g_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
+        result["roofline"] = {
+            "kernel": "k_gemm_stream (all five gathered linear maps of a layer)",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "launches": g_n, "avg_launch_us": 1e3 * g_ms / max(g_n, 1),
+            "alg_bytes_per_launch": g_bytes / max(g_n, 1),
+            "mfma_tflops": g_flops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0,
+            "mfma_frac": (g_flops / (g_ms * 1e-3) / 1e12) / MFMA_BF16_PEAK_TFLOPS if g_ms > 0 else 0.0,
+            "share_of_kernel_time": g_ms / total_ms if total_ms > 0 else 0.0,
+        }
+        result["kernels"] = {
+            k: {"launches": v["launches"], "ms_total": v["ms"],
+                "avg_us": 1e3 * v["ms"] / max(v["launches"], 1),
+                "GBps": (v["alg_bytes"] / (v["ms"] * 1e-3) / 1e9) if v["ms"] > 0 else 0.0,
+                "TFLOPs": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 else 0.0}
+            for k, v in stats.items()}
+        result["kernel_time_ms_per_step"] = total_ms / K
+
+    # the uncached forward on the same GPU: rho = 1, K_p = K_r = 1
+    if not args.no_uncached:
+        from oracle.dllm_cache_oracle import flops_uncached_step
+        unc = make_denoiser(binding, cfg, weights, rho=1.0, K_p=1, K_r=1)
+        for i in range(2):
+            unc.step(hidden[i], i, out)
+        torch.cuda.synchronize()
+        reps = 6
+        t0 = time.perf_counter()
+        for i in range(reps):
+            unc.step(hidden[i % cfg.steps], 2 + i, out)
+        torch.cuda.synchronize()
+        t_unc = (time.perf_counter() - t0) / reps
+        unc.close()
+        fl = cfg.B * flops_uncached_step(cfg.T, cfg.n, cfg.d, cfg.m)
+        result["uncached_gpu"] = {
+            "ms_per_step": 1e3 * t_unc, "steps_per_s": 1.0 / t_unc,
+            "tflops": fl / t_unc / 1e12, "mfma_frac": fl / t_unc / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "speedup_schedule": (elapsed / K) and t_unc / (elapsed / K),
+        }
+        if "ms_per_step_kind" in result and "adaptive" in result["ms_per_step_kind"]:
+            result["uncached_gpu"]["speedup_adaptive_step"] = 1e3 * t_unc / result["ms_per_step_kind"]["adaptive"]
+
+    den.close()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, weights, hidden_host)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

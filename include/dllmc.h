@@ -34,7 +34,7 @@ enum { DLLMC_F32 = 0, DLLMC_BF16 = 1 };
 enum {
   DLLMC_OK = 0,
   DLLMC_EINVAL = -1, /* bad dimension, rho outside [0,1], K_p/K_r < 1, null or misaligned pointer */
-  DLLMC_ESTATE = -2, /* first step is not step 0, or step_idx not increasing */
+  DLLMC_ESTATE = -2, /* first step is not step 0, or a non-zero step_idx that does not increase */
   DLLMC_EHIP = -3,   /* a HIP runtime call failed (see dllmc_last_hip_error) */
   DLLMC_ENOMEM = -4  /* workspace smaller than dllmc_workspace_bytes() */
 };
@@ -89,7 +89,8 @@ int32_t dllmc_num_selected(const dllmc_ctx* ctx);
 
 /* One denoising step (Sec. 3.2 "Iterative Steps").
  *   hidden_in  device [B, L_p+L_r, d], model dtype: embedded tokens of this step.
- *   step_idx   0 for the first call (fills both caches), then strictly increasing.
+ *   step_idx   0 for the first call (fills both caches), then strictly increasing; passing 0
+ *              again starts a new generation (a full refresh).
  *   hidden_out device [B, L_p+L_r, d], model dtype: residual stream after the last layer
  *              (no final norm).  Prompt rows are the values of the last prompt refresh.
  *   sel_idx    device [n_layers, B, L_r] int32, may be NULL.  For each layer and sequence the
@@ -108,11 +109,39 @@ int dllmc_read_cache(dllmc_ctx* ctx, int32_t layer, int32_t which, void* dst_dev
  * `dst_device`, float32 [n_layers, B, L_r]. */
 int dllmc_read_scores(dllmc_ctx* ctx, float* dst_device);
 
+/* Optional per-kernel timing.  While enabled, dllmc_step brackets each kernel launch with two
+ * HIP events on the context's stream.  dllmc_profile_read waits for the stream, adds the
+ * elapsed times to running totals per kernel class and copies the totals to `out`
+ * (DLLMC_NUM_KERNEL_CLASSES entries); reset != 0 clears the totals afterwards.  alg_bytes and
+ * flops are the algorithmic figures of the launches (for a gathered linear map: weights and
+ * activation rows read once, float32 result written once; 2*M*N*K flops). */
+enum {
+  DLLMC_KC_GEMM_V = 0, DLLMC_KC_GEMM_QK, DLLMC_KC_GEMM_O, DLLMC_KC_GEMM_GATE_UP,
+  DLLMC_KC_GEMM_DOWN, DLLMC_KC_ATTENTION, DLLMC_KC_SELECT, DLLMC_KC_ROW, DLLMC_KC_LISTS,
+  DLLMC_NUM_KERNEL_CLASSES
+};
+typedef struct {
+  int64_t launches;
+  double ms;
+  double alg_bytes;
+  double flops;
+} dllmc_kernel_stat;
+int dllmc_profile_enable(dllmc_ctx* ctx, int32_t on);
+int dllmc_profile_read(dllmc_ctx* ctx, dllmc_kernel_stat* out, int32_t reset);
+const char* dllmc_kernel_class_name(int32_t cls);
+
 int dllmc_destroy(dllmc_ctx* ctx);
 
 const char* dllmc_strerror(int code);
 /* hipError_t value of the most recent failed HIP call in this process, 0 if none. */
 int dllmc_last_hip_error(void);
+
+/* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
+ * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
+ * of the fused gate/up kernel, force_s number of contraction slices (0 = automatic), target_wg
+ * workgroups the automatic choice aims for.  Results are bit-reproducible for fixed settings;
+ * different settings change the float32 summation order only. */
+int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg);
 
 /* ---- single operations of the step, exposed for unit parity tests and micro-benchmarks ---- */
 

@@ -24,8 +24,10 @@ EXPORTS = (
     "dllmc_workspace_bytes", "dllmc_create", "dllmc_num_selected", "dllmc_step",
     "dllmc_read_cache", "dllmc_read_scores", "dllmc_destroy", "dllmc_strerror",
     "dllmc_last_hip_error", "dllmc_op_select", "dllmc_op_vverify", "dllmc_op_linear",
-    "dllmc_op_attention",
+    "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
+    "dllmc_set_gemm_tuning",
 )
+NUM_KERNEL_CLASSES = 9
 
 
 class dllmc_model(C.Structure):
@@ -38,6 +40,11 @@ class dllmc_model(C.Structure):
 class dllmc_layer_weights(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g",
                                           "w_gate", "w_up", "w_down")]
+
+
+class dllmc_kernel_stat(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("ms", C.c_double), ("alg_bytes", C.c_double),
+                ("flops", C.c_double)]
 
 
 class DllmcError(RuntimeError):
@@ -86,6 +93,14 @@ def lib() -> C.CDLL:
         L.dllmc_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_void_p]
+        L.dllmc_profile_enable.restype = C.c_int
+        L.dllmc_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+        L.dllmc_profile_read.restype = C.c_int
+        L.dllmc_profile_read.argtypes = [C.c_void_p, C.POINTER(dllmc_kernel_stat), C.c_int32]
+        L.dllmc_kernel_class_name.restype = C.c_char_p
+        L.dllmc_kernel_class_name.argtypes = [C.c_int32]
+        L.dllmc_set_gemm_tuning.restype = C.c_int
+        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 4
         _lib = L
     return _lib
 
@@ -168,6 +183,16 @@ class CachedDenoiser:
         _check(lib().dllmc_read_scores(self._h, out.data_ptr()), "dllmc_read_scores")
         return out
 
+    def profile_enable(self, on: bool) -> None:
+        _check(lib().dllmc_profile_enable(self._h, 1 if on else 0), "dllmc_profile_enable")
+
+    def profile_read(self, reset: bool = True) -> Dict[str, Dict[str, float]]:
+        arr = (dllmc_kernel_stat * NUM_KERNEL_CLASSES)()
+        _check(lib().dllmc_profile_read(self._h, arr, 1 if reset else 0), "dllmc_profile_read")
+        return {lib().dllmc_kernel_class_name(i).decode(): {
+            "launches": int(arr[i].launches), "ms": arr[i].ms, "alg_bytes": arr[i].alg_bytes,
+            "flops": arr[i].flops} for i in range(NUM_KERNEL_CLASSES)}
+
     def close(self) -> None:
         if self._h is not None:
             h, self._h = self._h, None
@@ -178,6 +203,10 @@ class CachedDenoiser:
             self.close()
         except Exception:
             pass
+
+
+def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1) -> None:
+    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg), "dllmc_set_gemm_tuning")
 
 
 def op_select(scores: torch.Tensor, k: int) -> torch.Tensor:

@@ -70,8 +70,16 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // of slices S it used (>= 1) so that consumers sum c_part[0..S) in order; c_part must hold
 // gemm_max_slices() * M * N floats.
 int gemm_max_slices();
+void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg);
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
                 const void* W1, int N0, int N, int K, float* c_part, hipStream_t st);
+
+// Fused gate/up projection with the SwiGLU product: u[i][j] = T(silu(a_i . w_gate_j) *
+// (a_i . w_up_j)), no slices, nothing but u written.  Returns false (and launches nothing)
+// when the shape or type is not handled; the caller then uses launch_gemm + launch_swiglu.
+bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int M,
+                        const void* w_gate, const void* w_up, int m, int K, void* u,
+                        hipStream_t st);
 
 // out[i][:] = sum_s c_part[s][i][:]
 void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, hipStream_t st);

@@ -100,6 +100,20 @@ struct dllmc_ctx {
   char* ws;
   bool have_scores;
 
+  // optional per-kernel timing with HIP events on the context's stream
+  bool profiling = false;
+  struct Span { hipEvent_t a, b; int cls; double bytes, flops; };
+  std::vector<Span> spans;           // recorded, not yet read back
+  std::vector<hipEvent_t> free_events;
+  dllmc_kernel_stat totals[DLLMC_NUM_KERNEL_CLASSES] = {};
+
+  hipEvent_t get_event() {
+    if (!free_events.empty()) { hipEvent_t e = free_events.back(); free_events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   void* cache(int which, int layer) const {
     switch (which) {
@@ -110,6 +124,26 @@ struct dllmc_ctx {
     }
   }
 };
+
+namespace {
+// Brackets the launches issued while it is alive with two events (only when profiling is on).
+struct Timed {
+  dllmc_ctx* c;
+  hipEvent_t a = nullptr, b = nullptr;
+  int cls; double bytes, flops;
+  Timed(dllmc_ctx* c_, int cls_, double bytes_, double flops_) : c(c_), cls(cls_), bytes(bytes_), flops(flops_) {
+    if (!c->profiling) return;
+    a = c->get_event();
+    b = c->get_event();
+    if (a && b) (void)hipEventRecord(a, c->st);
+  }
+  ~Timed() {
+    if (!c->profiling || !a || !b) return;
+    (void)hipEventRecord(b, c->st);
+    c->spans.push_back({a, b, cls, bytes, flops});
+  }
+};
+}  // namespace
 
 extern "C" {
 
@@ -182,7 +216,7 @@ int32_t dllmc_num_selected(const dllmc_ctx* ctx) { return ctx ? ctx->k_sel : DLL
 int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidden_out,
                int32_t* sel_idx, int32_t* n_sel) {
   if (!c || !hidden_in || !hidden_out || step_idx < 0) return DLLMC_EINVAL;
-  if ((c->last_step < 0 && step_idx != 0) || step_idx <= c->last_step) return DLLMC_ESTATE;
+  if (step_idx != 0 && (c->last_step < 0 || step_idx <= c->last_step)) return DLLMC_ESTATE;
   (void)hipGetLastError();  // do not inherit a stale error
 
   const dllmc_model& m = c->m;
@@ -217,47 +251,100 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   void* prompt_out = c->ws + c->lay.off_prompt_out;
   const float2* rope_tab = c->at<float2>(c->lay.off_rope);
 
-  // row lists of this step
-  launch_iota_rows(carried, nullptr, B, n, P ? 0 : L_p, carried_per_seq, carried_per_seq, 0, st);
-  if (P) launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq, 0, st);
-  if (Rf) {
-    launch_iota_rows(rows_R, inv, B, n, L_p, L_r, per_seq, sel_off, st);
-    if (sel_idx) launch_fill_sel_identity(sel_idx, T * B, L_r, st);
-  }
+  const double esz = static_cast<double>(c->lay.esz);
+  // algorithmic bytes / flops of one gathered linear map: weights, activations in, float32 out
+  auto gemm_bytes = [&](double M, double N, double K) { return (N * K + M * K) * esz + M * N * 4.0; };
+  auto gemm_flops = [&](double M, double N, double K) { return 2.0 * M * N * K; };
 
-  launch_embed_norm(ra, hidden_in, carried, Mc, c->layers[0].attn_norm_g, x, h, st);
+  // row lists of this step
+  {
+    Timed t(c, DLLMC_KC_LISTS, 0, 0);
+    launch_iota_rows(carried, nullptr, B, n, P ? 0 : L_p, carried_per_seq, carried_per_seq, 0, st);
+    if (P) launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq, 0, st);
+    if (Rf) {
+      launch_iota_rows(rows_R, inv, B, n, L_p, L_r, per_seq, sel_off, st);
+      if (sel_idx) launch_fill_sel_identity(sel_idx, T * B, L_r, st);
+    }
+  }
+  {
+    Timed t(c, DLLMC_KC_ROW, Mc * d * (2.0 * esz + 4.0), 0);
+    launch_embed_norm(ra, hidden_in, carried, Mc, c->layers[0].attn_norm_g, x, h, st);
+  }
 
   for (int l = 0; l < T; ++l) {
     const dllmc_layer_weights& w = c->layers[l];
     void* Kc = c->cache(0, l);
     void* Vc = c->cache(1, l);
     // V-verify: V for every carried row, score against the cache, overwrite the cache
-    int S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, st);
+    int S;
+    {
+      Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
+      S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, st);
+    }
     float* sc = scores + static_cast<size_t>(l) * B * L_r;
-    launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, Rf ? nullptr : sc, st);
-    if (!Rf)
+    {
+      Timed t(c, DLLMC_KC_ROW, Mc * d_kv * (4.0 + 2.0 * esz), 0);
+      launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, Rf ? nullptr : sc, st);
+    }
+    if (!Rf) {
+      Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + c->k_sel * 8.0 + L_r * 4.0), 0);
       launch_select(sc, B, L_r, c->k_sel,
                     sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
                     per_seq, sel_off, inv, n, L_p, st);
+    }
     S = 1;
     if (M_R > 0) {
-      S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, st);
-      launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, Kc, st);
-      launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf, st);
-      S = launch_gemm(dt, abuf, d_q, nullptr, M_R, w.wo, nullptr, d, d, d_q, cws, st);
+      {
+        Timed t(c, DLLMC_KC_GEMM_QK, gemm_bytes(M_R, d_q + d_kv, d), gemm_flops(M_R, d_q + d_kv, d));
+        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, st);
+      }
+      {
+        Timed t(c, DLLMC_KC_ROW, M_R * (d_q + d_kv) * (4.0 + esz), 0);
+        launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, Kc, st);
+      }
+      {
+        // queries in and out once, every sequence's K and V once per group of query heads
+        Timed t(c, DLLMC_KC_ATTENTION, (2.0 * M_R * d_q + 2.0 * B * n * d_kv) * esz,
+                4.0 * M_R * static_cast<double>(n) * d_q);
+        launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf, st);
+      }
+      {
+        Timed t(c, DLLMC_KC_GEMM_O, gemm_bytes(M_R, d, d_q), gemm_flops(M_R, d, d_q));
+        S = launch_gemm(dt, abuf, d_q, nullptr, M_R, w.wo, nullptr, d, d, d_q, cws, st);
+      }
     }
-    launch_o_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
+    {
+      Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + esz) + M_R * d * (4.0 + 2.0 * esz), 0);
+      launch_o_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
+    }
     if (M_R > 0) {
-      S = launch_gemm(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, 2 * mf, d, cws, st);
-      launch_swiglu(dt, cws, S, M_R, mf, ubuf, st);
-      S = launch_gemm(dt, ubuf, mf, nullptr, M_R, w.w_down, nullptr, d, d, mf, cws, st);
+      bool fused;
+      {
+        Timed t(c, DLLMC_KC_GEMM_GATE_UP, gemm_bytes(M_R, 2.0 * mf, d), gemm_flops(M_R, 2.0 * mf, d));
+        fused = launch_gemm_swiglu(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, d, ubuf, st);
+        if (!fused) S = launch_gemm(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, 2 * mf, d, cws, st);
+      }
+      if (!fused) {
+        Timed t(c, DLLMC_KC_ROW, M_R * mf * (8.0 + esz), 0);
+        launch_swiglu(dt, cws, S, M_R, mf, ubuf, st);
+      }
+      {
+        Timed t(c, DLLMC_KC_GEMM_DOWN, gemm_bytes(M_R, d, mf), gemm_flops(M_R, d, mf));
+        S = launch_gemm(dt, ubuf, mf, nullptr, M_R, w.w_down, nullptr, d, d, mf, cws, st);
+      }
     }
     const bool last = (l == T - 1);
-    launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(3, l), x,
-                         last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
-                         (last && P) ? prompt_out : nullptr, st);
+    {
+      Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + 2.0 * esz) + M_R * d * (4.0 + esz), 0);
+      launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(3, l), x,
+                           last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
+                           (last && P) ? prompt_out : nullptr, st);
+    }
   }
-  if (!P) launch_copy_prompt(ra, B, prompt_out, hidden_out, st);
+  if (!P) {
+    Timed t(c, DLLMC_KC_LISTS, 2.0 * B * L_p * d * esz, 0);
+    launch_copy_prompt(ra, B, prompt_out, hidden_out, st);
+  }
 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(e);
@@ -285,9 +372,47 @@ int dllmc_read_scores(dllmc_ctx* c, float* dst_device) {
   return DLLMC_OK;
 }
 
+int dllmc_profile_enable(dllmc_ctx* c, int32_t on) {
+  if (!c) return DLLMC_EINVAL;
+  c->profiling = on != 0;
+  return DLLMC_OK;
+}
+
+int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
+  if (!c || !out) return DLLMC_EINVAL;
+  HIP_TRY(hipStreamSynchronize(c->st));
+  for (const dllmc_ctx::Span& sp : c->spans) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+    dllmc_kernel_stat& t = c->totals[sp.cls];
+    t.launches += 1;
+    t.ms += ms;
+    t.alg_bytes += sp.bytes;
+    t.flops += sp.flops;
+    c->free_events.push_back(sp.a);
+    c->free_events.push_back(sp.b);
+  }
+  c->spans.clear();
+  std::memcpy(out, c->totals, sizeof(c->totals));
+  if (reset) std::memset(c->totals, 0, sizeof(c->totals));
+  return DLLMC_OK;
+}
+
+const char* dllmc_kernel_class_name(int32_t cls) {
+  static const char* names[DLLMC_NUM_KERNEL_CLASSES] = {
+      "gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down", "attention", "select",
+      "row_kernels", "lists_and_copies"};
+  return (cls >= 0 && cls < DLLMC_NUM_KERNEL_CLASSES) ? names[cls] : "?";
+}
+
 int dllmc_destroy(dllmc_ctx* c) {
   if (!c) return DLLMC_EINVAL;
   hipError_t e = hipStreamSynchronize(c->st);  // the workspace goes back to the caller idle
+  for (const dllmc_ctx::Span& sp : c->spans) {
+    (void)hipEventDestroy(sp.a);
+    (void)hipEventDestroy(sp.b);
+  }
+  for (hipEvent_t ev : c->free_events) (void)hipEventDestroy(ev);
   delete c;
   if (e != hipSuccess) return hip_fail(e);
   return DLLMC_OK;
@@ -305,6 +430,11 @@ const char* dllmc_strerror(int code) {
 }
 
 int dllmc_last_hip_error(void) { return g_last_hip_error; }
+
+int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg) {
+  gemm_set_tuning(nw, nw_dual, force_s, target_wg);
+  return DLLMC_OK;
+}
 
 // ---- single operations ------------------------------------------------------------------
 

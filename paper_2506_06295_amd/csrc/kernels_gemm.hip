@@ -88,84 +88,145 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 }
 
 // ------------------------------------------------------------------------------------
+// k_gemm_stream<NW, KC, DUAL>
 // Workgroup = NW wavefronts; tile = 64 activation rows x (16*NW) output columns; wavefront w
-// owns 16 columns and all 64 rows (four 16x16 accumulators of v_mfma_f32_16x16x32_bf16).
-// Per 128-wide step of the contraction index, lane (n = lane%16, g = lane/16) holds
-// W[col n][k0 + 32g .. k0 + 32g + 31]; its c-th 16-byte piece is MFMA step c, and the A
-// operand is read from LDS with the same (g, c) -> k mapping, so the order in which the
-// contraction index is visited differs from 0..K-1 but is the same for both operands.
-template <int NW>
+// owns 16 columns and all 64 rows (four 16x16 accumulators of v_mfma_f32_16x16x32_bf16 per
+// weight matrix).  The workgroup's slice of the contraction index is walked in phases of KC:
+// the activation tile of phase p+1 is fetched into registers while phase p is multiplied and
+// is written to the other LDS buffer at the end of the phase (one barrier per phase).  The
+// weight stream is prefetched one 128-wide step ahead and runs across phase boundaries.
+// Lane (n = lane%16, g = lane/16) holds, for MFMA step c of a 128-wide step, the eight
+// weights W[col n][k0 + 32c + 8g ..+8]; the A operand is read from LDS at the same offsets.
+//   DUAL = 0: columns [0,N0) come from W0, [N0,N) from W1; float32 partial sums are stored
+//             to slice blockIdx.z of C.
+//   DUAL = 1: every lane streams row n of W0 (gate) and row n of W1 (up) and the epilogue
+//             stores bf16(silu(gate) * up) to U[M, N] (SwiGLU, complexity appendix of the
+//             paper); needs a single slice.
+template <int NW, int KC, int DUAL>
 __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, int N0, int N, int K,
-    int k_per_slice, int KC, float* __restrict__ C) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem_raw);
-  const int lds_stride = KC + 8;  // +16 bytes: consecutive rows start 4 banks apart
+    int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
+  constexpr int LS = KC + 8;                 // LDS row stride: rows start 4 banks apart
+  constexpr int CPR = KC / 8;                // 16-byte chunks per activation row and phase
+  constexpr int NCH = 64 * CPR / (NW * 64);  // chunks staged per thread and phase
+  constexpr int NB = DUAL ? 2 : 1;
+  static_assert((64 * CPR) % (NW * 64) == 0 && NCH >= 1, "staging must divide evenly");
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][64 * LS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int m0 = blockIdx.y * 64;
   const int kbeg = blockIdx.z * k_per_slice;
-  const int kend = min(K, kbeg + k_per_slice);
+  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KC
+  const int nph = klen / KC;
   const int ncol = blockIdx.x * (16 * NW) + wave * 16 + ln;  // < N: N % (16*NW) == 0
-  const bf16_t* wrow = ncol < N0 ? W0 + static_cast<size_t>(ncol) * K
-                                 : W1 + static_cast<size_t>(ncol - N0) * K;
-  f32x4 acc[4];
+  const bf16_t* wp[NB];
+  if (DUAL) {
+    wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + lg * 8;
+    wp[NB - 1] = W1 + static_cast<size_t>(ncol) * K + kbeg + lg * 8;
+  } else {
+    wp[0] = (ncol < N0 ? W0 + static_cast<size_t>(ncol) * K
+                       : W1 + static_cast<size_t>(ncol - N0) * K) + kbeg + lg * 8;
+  }
+  // the activation chunks this thread stages: same (row, chunk) in every phase
+  const bf16_t* asrc[NCH];
+  int adst[NCH];
+  bool aval[NCH];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NCH; ++j) {
+    const int e = threadIdx.x + j * NW * 64;
+    const int r = e / CPR, c = e % CPR;
+    const int m = m0 + r;
+    aval[j] = m < M;
+    const int row = aval[j] ? (rows ? rows[m] : m) : 0;
+    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + c * 8;
+    adst[j] = r * LS + c * 8;
+  }
+  f32x4 acc[NB][4];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int kp = kbeg; kp < kend; kp += KC) {
-    const int kc = min(KC, kend - kp);  // multiple of 128
-    __syncthreads();
-    {
-      const int cpr = kc / 8;  // 16-byte chunks per row
-      for (int e = threadIdx.x; e < 64 * cpr; e += NW * 64) {
-        const int r = e / cpr, c = e - r * cpr;
-        const int m = m0 + r;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (m < M) {
-          const int row = rows ? rows[m] : m;
-          v = *reinterpret_cast<const uint4*>(A + static_cast<size_t>(row) * lda + kp + c * 8);
-        }
-        *reinterpret_cast<uint4*>(As + r * lds_stride + c * 8) = v;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j]);
+    *reinterpret_cast<uint4*>(&As[0][adst[j]]) = v;
+  }
+  uint4 bn[NB][4];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) bn[b][c] = *reinterpret_cast<const uint4*>(wp[b] + c * 32);
+  __syncthreads();
+
+  for (int ph = 0; ph < nph; ++ph) {
+    const bool more = ph + 1 < nph;
+    uint4 av[NCH];
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        av[j] = make_uint4(0u, 0u, 0u, 0u);
+        if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + (ph + 1) * KC);
       }
     }
-    __syncthreads();
-
-    const bf16_t* wp = wrow + kp + lg * 32;
-    const bf16_t* ap = As + ln * lds_stride + lg * 32;
-    uint4 bn[4];
+    const bf16_t* ap = &As[ph & 1][ln * LS + lg * 8];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) bn[c] = *reinterpret_cast<const uint4*>(wp + c * 8);
-    for (int ks = 0; ks < kc; ks += 128) {
-      uint4 b[4];
+    for (int ks = 0; ks < KC; ks += 128) {
+      uint4 bc[NB][4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) b[c] = bn[c];
-      if (ks + 128 < kc) {
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bn[c] = *reinterpret_cast<const uint4*>(wp + ks + 128 + c * 8);
+        for (int c = 0; c < 4; ++c) bc[b][c] = bn[b][c];
+      const int knext = ph * KC + ks + 128;
+      if (knext < klen) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            bn[b][c] = *reinterpret_cast<const uint4*>(wp[b] + knext + c * 32);
       }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bf16x8 bf = __builtin_bit_cast(bf16x8, b[c]);
+      for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-          const bf16x8 af =
-              *reinterpret_cast<const bf16x8*>(ap + mb * 16 * lds_stride + ks + c * 8);
-          acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf, acc[mb], 0, 0, 0);
+          const bf16x8 af = *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + ks + c * 32);
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                af, __builtin_bit_cast(bf16x8, bc[b][c]), acc[b][mb], 0, 0, 0);
         }
-      }
     }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j)
+        *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][adst[j]]) = av[j];
+    }
+    __syncthreads();
   }
 
-  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
+  if (DUAL) {
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + mb * 16 + lg * 4 + i;
-      if (m < M) Cs[static_cast<size_t>(m) * N + ncol] = acc[mb][i];
-    }
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + mb * 16 + lg * 4 + i;
+        if (m < M) {
+          const float g = acc[0][mb][i], up = acc[NB - 1][mb][i];
+          U[static_cast<size_t>(m) * N + ncol] = f32_to_bf16(g / (1.0f + expf(-g)) * up);
+        }
+      }
+  } else {
+    float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + mb * 16 + lg * 4 + i;
+        if (m < M) Cs[static_cast<size_t>(m) * N + ncol] = acc[0][mb][i];
+      }
+  }
 }
 
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
@@ -186,21 +247,42 @@ void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, 
 
 // ------------------------------------------------------------------------------------
 namespace {
-constexpr int kStreamNW = 8;      // wavefronts per workgroup of the streaming kernel
-constexpr int kStreamKC = 512;    // contraction-index extent staged in LDS per phase
-bool g_attr_set = false;
+struct GemmTuning {
+  int nw = 8;          // wavefronts per workgroup (4 or 8) of the single-matrix kernel
+  int nw_dual = 4;     // same for the fused gate/up kernel
+  int force_s = 0;     // > 0: number of slices of the contraction index
+  int target_wg = 256; // workgroups the automatic slice count aims for
+} g_tune;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <int NW, int KC, int DUAL>
+void launch_stream(dim3 grid, hipStream_t st, const bf16_t* A, int lda, const int* rows, int M,
+                   const bf16_t* W0, const bf16_t* W1, int N0, int N, int K, int kps, float* C,
+                   bf16_t* U) {
+  hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
+                     W1, N0, N, K, kps, C, U);
+}
+
+bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const void* W1, int K) {
+  return dtype == 1 && (K % 128 == 0) && (lda % 8 == 0) && aligned16(A) && aligned16(W0) &&
+         (W1 == nullptr || aligned16(W1));
+}
 }  // namespace
+
+void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
+  if (nw == 4 || nw == 8) g_tune.nw = nw;
+  if (nw_dual == 4 || nw_dual == 8) g_tune.nw_dual = nw_dual;
+  if (force_s >= 0) g_tune.force_s = force_s;
+  if (target_wg > 0) g_tune.target_wg = target_wg;
+}
 
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
                 const void* W1, int N0, int N, int K, float* c_part, hipStream_t st) {
   if (M <= 0 || N <= 0) return 1;
-  const int BN = 16 * kStreamNW;
-  const bool stream_ok = dtype == 1 && (K % 128 == 0) && (N % BN == 0) && (N0 % BN == 0) &&
-                         (lda % 8 == 0) && aligned16(A) && aligned16(W0) &&
-                         (W1 == nullptr || aligned16(W1));
-  if (!stream_ok) {
+  const int NW = g_tune.nw;
+  const int BN = 16 * NW;
+  if (!(stream_shape_ok(dtype, A, lda, W0, W1, K) && N % BN == 0 && N0 % BN == 0)) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
     if (dtype == 1)
       hipLaunchKernelGGL(k_gemm_simple<bf16_t>, grid, dim3(256), 0, st,
@@ -213,25 +295,50 @@ int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const
                          static_cast<const float*>(W1), N0, N, K, c_part);
     return 1;
   }
+  const int KC = (K % 256 == 0) ? 256 : 128;
   const int mt = (M + 63) / 64, nt = N / BN;
-  // enough workgroups for two per CU (256 CUs) when the tile count alone does not give them
-  int S = (512 + mt * nt - 1) / (mt * nt);
+  int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + mt * nt - 1) / (mt * nt);
   S = S < 1 ? 1 : (S > kMaxSlices ? kMaxSlices : S);
-  int kps = ((K + S - 1) / S + 127) / 128 * 128;
-  if (kps < 256) kps = 256;
+  int kps = ((K + S - 1) / S + KC - 1) / KC * KC;
   if (kps > K) kps = K;
   S = (K + kps - 1) / kps;
-  const int KC = kps < kStreamKC ? kps : kStreamKC;
-  const size_t lds = static_cast<size_t>(64) * (KC + 8) * sizeof(bf16_t);
-  if (!g_attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_stream<kStreamNW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-    g_attr_set = true;
+  const dim3 grid(nt, mt, S);
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w0 = static_cast<const bf16_t*>(W0);
+  const bf16_t* w1 = static_cast<const bf16_t*>(W1);
+#define DLLMC_GS(NWv, KCv) \
+  launch_stream<NWv, KCv, 0>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, kps, c_part, nullptr)
+  if (NW == 8) {
+    if (KC == 256) DLLMC_GS(8, 256); else DLLMC_GS(8, 128);
+  } else {
+    if (KC == 256) DLLMC_GS(4, 256); else DLLMC_GS(4, 128);
   }
-  hipLaunchKernelGGL(k_gemm_stream<kStreamNW>, dim3(nt, mt, S), dim3(kStreamNW * 64), lds, st,
-                     static_cast<const bf16_t*>(A), lda, rows, M, static_cast<const bf16_t*>(W0),
-                     static_cast<const bf16_t*>(W1), N0, N, K, kps, KC, c_part);
+#undef DLLMC_GS
   return S;
+}
+
+bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int M,
+                        const void* w_gate, const void* w_up, int m, int K, void* u,
+                        hipStream_t st) {
+  if (M <= 0 || m <= 0) return true;
+  const int NW = g_tune.nw_dual;
+  if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % (16 * NW) == 0) || M > 128)
+    return false;
+  const int KC = (K % 256 == 0) ? 256 : 128;
+  const dim3 grid(m / (16 * NW), (M + 63) / 64, 1);
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
+  const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
+  bf16_t* uo = static_cast<bf16_t*>(u);
+#define DLLMC_GD(NWv, KCv) \
+  launch_stream<NWv, KCv, 1>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
+  if (NW == 8) {
+    if (KC == 256) DLLMC_GD(8, 256); else DLLMC_GD(8, 128);
+  } else {
+    if (KC == 256) DLLMC_GD(4, 256); else DLLMC_GD(4, 128);
+  }
+#undef DLLMC_GD
+  return true;
 }
 
 }  // namespace dllmc

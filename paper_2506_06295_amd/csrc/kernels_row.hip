@@ -4,6 +4,9 @@
 // wavefront shuffles first, then a fixed-order sum over the four wavefronts.  They also
 // add up the float32 slices the split contraction of the GEMMs leaves behind, round once to
 // the storage type, and do the cache scatter, so no value makes an extra trip through HBM.
+// All global accesses are 16-byte (or 8-byte for bf16) vectors when the row width allows it
+// (V = 4), issued for the whole row before the first use so that one memory round trip
+// covers a row; V = 1 is the fallback for widths that are not multiples of four.
 #include "common.hpp"
 
 namespace dllmc {
@@ -12,16 +15,93 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kNW = kThreads / kWave;
+constexpr int kRegVecs = 4;  // vectors of a row a thread keeps in registers (rows up to 4096 wide)
 
-__device__ __forceinline__ float sum_slices(const float* __restrict__ c_part, int S, size_t stride,
-                                            size_t off) {
-  float t = c_part[off];
-  for (int s = 1; s < S; ++s) t += c_part[static_cast<size_t>(s) * stride + off];
+template <int V> struct Vec { float v[V]; };
+
+template <int V> __device__ __forceinline__ Vec<V> ld_f32(const float* p);
+template <> __device__ __forceinline__ Vec<1> ld_f32<1>(const float* p) { return {{*p}}; }
+template <> __device__ __forceinline__ Vec<4> ld_f32<4>(const float* p) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  return {{t.x, t.y, t.z, t.w}};
+}
+template <int V> __device__ __forceinline__ void st_f32(float* p, const Vec<V>& a);
+template <> __device__ __forceinline__ void st_f32<1>(float* p, const Vec<1>& a) { *p = a.v[0]; }
+template <> __device__ __forceinline__ void st_f32<4>(float* p, const Vec<4>& a) {
+  *reinterpret_cast<float4*>(p) = make_float4(a.v[0], a.v[1], a.v[2], a.v[3]);
+}
+
+template <typename T, int V> struct IO;
+template <> struct IO<float, 1> {
+  static __device__ __forceinline__ Vec<1> ld(const float* p) { return {{*p}}; }
+  static __device__ __forceinline__ void st(float* p, const Vec<1>& a) { *p = a.v[0]; }
+};
+template <> struct IO<float, 4> {
+  static __device__ __forceinline__ Vec<4> ld(const float* p) { return ld_f32<4>(p); }
+  static __device__ __forceinline__ void st(float* p, const Vec<4>& a) { st_f32<4>(p, a); }
+};
+template <> struct IO<bf16_t, 1> {
+  static __device__ __forceinline__ Vec<1> ld(const bf16_t* p) { return {{bf16_to_f32(*p)}}; }
+  static __device__ __forceinline__ void st(bf16_t* p, const Vec<1>& a) { *p = f32_to_bf16(a.v[0]); }
+};
+template <> struct IO<bf16_t, 4> {
+  static __device__ __forceinline__ Vec<4> ld(const bf16_t* p) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    return {{__uint_as_float(t.x << 16), __uint_as_float(t.x & 0xffff0000u),
+             __uint_as_float(t.y << 16), __uint_as_float(t.y & 0xffff0000u)}};
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, const Vec<4>& a) {
+    uint2 t;
+    t.x = static_cast<uint32_t>(f32_to_bf16(a.v[0])) | (static_cast<uint32_t>(f32_to_bf16(a.v[1])) << 16);
+    t.y = static_cast<uint32_t>(f32_to_bf16(a.v[2])) | (static_cast<uint32_t>(f32_to_bf16(a.v[3])) << 16);
+    *reinterpret_cast<uint2*>(p) = t;
+  }
+};
+
+// sum of the S slices at one position, in slice order
+template <int V>
+__device__ __forceinline__ Vec<V> sum_slices(const float* __restrict__ c_part, int S, size_t stride,
+                                             size_t off) {
+  Vec<V> t = ld_f32<V>(c_part + off);
+  for (int s = 1; s < S; ++s) {
+    const Vec<V> u = ld_f32<V>(c_part + static_cast<size_t>(s) * stride + off);
+#pragma unroll
+    for (int e = 0; e < V; ++e) t.v[e] += u.v[e];
+  }
   return t;
 }
 
+// Slice sums for the kRegVecs vectors of this thread inside the chunk starting at column c0
+// (vector `it` sits at column c0 + (it*kThreads + threadIdx.x)*V).  All loads are independent
+// and unrolled so that they are in flight together; the additions keep slice order.
+constexpr int kMaxSlicesRow = 8;
+template <int V>
+__device__ __forceinline__ void sum_slices_chunk(const float* __restrict__ c_part, int S,
+                                                 size_t stride, size_t row_off, int c0, int width,
+                                                 Vec<V> (&out)[kRegVecs]) {
+#pragma unroll
+  for (int it = 0; it < kRegVecs; ++it)
+#pragma unroll
+    for (int e = 0; e < V; ++e) out[it].v[e] = 0.f;
+#pragma unroll
+  for (int s = 0; s < kMaxSlicesRow; ++s) {
+    if (s < S) {
+#pragma unroll
+      for (int it = 0; it < kRegVecs; ++it) {
+        const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+        if (c < width) {
+          const Vec<V> u = ld_f32<V>(c_part + static_cast<size_t>(s) * stride + row_off + c);
+#pragma unroll
+          for (int e = 0; e < V; ++e) out[it].v[e] += u.v[e];
+        }
+      }
+    }
+  }
+}
+constexpr int kChunk(int V) { return kRegVecs * kThreads * V; }
+
 // ---- prologue: residual stream from the embedded tokens, first attention norm ----------
-template <typename T>
+template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_embed_norm(const T* __restrict__ hidden_in,
                                                          const int* __restrict__ rows, int d,
                                                          float eps, const T* __restrict__ gain,
@@ -30,20 +110,27 @@ __global__ __launch_bounds__(kThreads) void k_embed_norm(const T* __restrict__ h
   const int row = rows[blockIdx.x];
   const T* src = hidden_in + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
+  T* hr = h + static_cast<size_t>(row) * d;
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    const float v = ldf(src + c);
-    xr[c] = v;
-    ss += v * v;
+  for (int c = threadIdx.x * V; c < d; c += kThreads * V) {
+    const Vec<V> a = IO<T, V>::ld(src + c);
+    st_f32<V>(xr + c, a);
+#pragma unroll
+    for (int e = 0; e < V; ++e) ss += a.v[e] * a.v[e];
   }
   ss = block_sum<kNW>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
-  T* hr = h + static_cast<size_t>(row) * d;
-  for (int c = threadIdx.x; c < d; c += kThreads) stf(hr + c, xr[c] * rstd * ldf(gain + c));
+  for (int c = threadIdx.x * V; c < d; c += kThreads * V) {
+    Vec<V> a = ld_f32<V>(xr + c);  // this thread's own stores
+    const Vec<V> g = IO<T, V>::ld(gain + c);
+#pragma unroll
+    for (int e = 0; e < V; ++e) a.v[e] = a.v[e] * rstd * g.v[e];
+    IO<T, V>::st(hr + c, a);
+  }
 }
 
 // ---- V-verify epilogue: round V_new, cosine against the cached row, overwrite the cache --
-template <typename T>
+template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict__ c_part, int S,
                                                          size_t slice_stride,
                                                          const int* __restrict__ rows, int d_kv,
@@ -56,15 +143,33 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
   const int pos = row % n;
   const bool scored = (score != nullptr) && (pos >= L_p);
   float dot = 0.f, nn = 0.f, no = 0.f;
-  for (int c = threadIdx.x; c < d_kv; c += kThreads) {
-    const float v = roundf_to<T>(sum_slices(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv + c));
+  for (int c0 = 0; c0 < d_kv; c0 += kChunk(V)) {
+    Vec<V> v[kRegVecs], o[kRegVecs];
+    sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv, c0, d_kv, v);
     if (scored) {
-      const float o = ldf(vc + c);
-      dot += v * o;
-      nn += v * v;
-      no += o * o;
+#pragma unroll
+      for (int it = 0; it < kRegVecs; ++it) {
+        const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+        if (c < d_kv) o[it] = IO<T, V>::ld(vc + c);
+      }
     }
-    stf(vc + c, v);
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) {
+      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      if (c < d_kv) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) v[it].v[e] = roundf_to<T>(v[it].v[e]);
+        if (scored) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) {
+            dot += v[it].v[e] * o[it].v[e];
+            nn += v[it].v[e] * v[it].v[e];
+            no += o[it].v[e] * o[it].v[e];
+          }
+        }
+        IO<T, V>::st(vc + c, v[it]);
+      }
+    }
   }
   if (scored) {
     dot = block_sum<kNW>(dot, red);
@@ -80,44 +185,35 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
 }
 
 // ---- Q/K epilogue: RoPE at the row's absolute position, Q to the compact buffer, K scatter --
+// grid (rows, query heads + kv heads), one wavefront per (row, head), one lane per pair.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void k_qk_finalize(const float* __restrict__ c_part, int S,
-                                                          size_t slice_stride,
-                                                          const int* __restrict__ rows, int n,
-                                                          int d_q, int d_kv, int d_h,
-                                                          const float2* __restrict__ rope_tab,
-                                                          T* __restrict__ q_out,
-                                                          T* __restrict__ k_cache) {
-  const int i = blockIdx.x;
+__global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_part, int S,
+                                                    size_t slice_stride,
+                                                    const int* __restrict__ rows, int n, int d_q,
+                                                    int d_kv, int d_h,
+                                                    const float2* __restrict__ rope_tab,
+                                                    T* __restrict__ q_out, T* __restrict__ k_cache) {
+  const int i = blockIdx.x, head = blockIdx.y;
   const int row = rows[i];
   const int pos = row % n;
   const int half = d_h / 2;
   const int width = d_q + d_kv;
   const float2* tab = rope_tab + static_cast<size_t>(pos) * half;
-  T* qr = q_out + static_cast<size_t>(i) * d_q;
-  T* kr = k_cache + static_cast<size_t>(row) * d_kv;
-  // one thread per rotation pair
-  for (int p = threadIdx.x; p < width / 2; p += kThreads) {
-    const int head = p / half, t = p - head * half;
-    const int c0 = head * d_h + t;  // column of the pair's first element in [Q | K]
-    const size_t off = static_cast<size_t>(i) * width + c0;
-    const float a = sum_slices(c_part, S, slice_stride, off);
-    const float b = sum_slices(c_part, S, slice_stride, off + half);
+  const int c0 = head * d_h;  // first column of the head inside [Q | K]
+  T* dst = c0 < d_q ? q_out + static_cast<size_t>(i) * d_q + c0
+                    : k_cache + static_cast<size_t>(row) * d_kv + (c0 - d_q);
+  for (int t = threadIdx.x; t < half; t += 64) {
+    const size_t off = static_cast<size_t>(i) * width + c0 + t;
+    const float a = sum_slices<1>(c_part, S, slice_stride, off).v[0];
+    const float b = sum_slices<1>(c_part, S, slice_stride, off + half).v[0];
     const float2 cs = tab[t];
-    const float ra = a * cs.x - b * cs.y;
-    const float rb = b * cs.x + a * cs.y;
-    if (c0 < d_q) {
-      stf(qr + c0, ra);
-      stf(qr + c0 + half, rb);
-    } else {
-      stf(kr + (c0 - d_q), ra);
-      stf(kr + (c0 - d_q) + half, rb);
-    }
+    stf(dst + t, a * cs.x - b * cs.y);
+    stf(dst + t + half, b * cs.x + a * cs.y);
   }
 }
 
 // ---- output projection epilogue + residual + FFN norm ------------------------------------
-template <typename T>
+template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict__ c_part, int S,
                                                          size_t slice_stride,
                                                          const int* __restrict__ carried,
@@ -131,27 +227,54 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
   const int ci = inv[row];
   T* ac = attn_cache + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
+  Vec<V> keep[kRegVecs];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    float a;
-    if (ci >= 0) {
-      a = roundf_to<T>(sum_slices(c_part, S, slice_stride, static_cast<size_t>(ci) * d + c));
-      stf(ac + c, a);
-    } else {
-      a = ldf(ac + c);
+  for (int c0 = 0; c0 < d; c0 += kChunk(V)) {
+    Vec<V> a[kRegVecs], xv[kRegVecs];
+    if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, a);
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) {
+      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      if (c < d) {
+        if (ci < 0) a[it] = IO<T, V>::ld(ac + c);
+        xv[it] = ld_f32<V>(xr + c);
+      }
     }
-    const float v = xr[c] + a;
-    xr[c] = v;
-    ss += v * v;
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) {
+      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      if (c < d) {
+        if (ci >= 0) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) a[it].v[e] = roundf_to<T>(a[it].v[e]);
+          IO<T, V>::st(ac + c, a[it]);
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          xv[it].v[e] += a[it].v[e];
+          ss += xv[it].v[e] * xv[it].v[e];
+        }
+        st_f32<V>(xr + c, xv[it]);
+        if (c0 == 0) keep[it] = xv[it];
+      }
+    }
   }
+  int it = 0;
   if (ci < 0) return;  // uniform over the workgroup
   ss = block_sum<kNW>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
   T* gr = g_out + static_cast<size_t>(ci) * d;
-  for (int c = threadIdx.x; c < d; c += kThreads) stf(gr + c, xr[c] * rstd * ldf(gain + c));
+  it = 0;
+  for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
+    Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
+    const Vec<V> g = IO<T, V>::ld(gain + c);
+#pragma unroll
+    for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * g.v[e];
+    IO<T, V>::st(gr + c, xv);
+  }
 }
 
-// ---- SwiGLU product ---------------------------------------------------------------------
+// ---- SwiGLU product (only when the fused gate/up kernel does not apply) -------------------
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c_part, int S,
                                                      size_t slice_stride, int m,
@@ -160,13 +283,13 @@ __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c
   const int j = blockIdx.x * kThreads + threadIdx.x;
   if (j >= m) return;
   const size_t off = static_cast<size_t>(i) * 2 * m + j;
-  const float g = sum_slices(c_part, S, slice_stride, off);
-  const float up = sum_slices(c_part, S, slice_stride, off + m);
+  const float g = sum_slices<1>(c_part, S, slice_stride, off).v[0];
+  const float up = sum_slices<1>(c_part, S, slice_stride, off + m).v[0];
   stf(u + static_cast<size_t>(i) * m + j, g / (1.0f + expf(-g)) * up);
 }
 
 // ---- down projection epilogue + residual + next layer's attention norm / step output ------
-template <typename T>
+template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_down_finalize(
     const float* __restrict__ c_part, int S, size_t slice_stride, const int* __restrict__ carried,
     const int* __restrict__ inv, int d, int n, int L_p, float eps, T* __restrict__ ffn_cache,
@@ -177,34 +300,62 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
   const int ci = inv[row];
   T* fc = ffn_cache + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
+  Vec<V> keep[kRegVecs];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += kThreads) {
-    float f;
-    if (ci >= 0) {
-      f = roundf_to<T>(sum_slices(c_part, S, slice_stride, static_cast<size_t>(ci) * d + c));
-      stf(fc + c, f);
-    } else {
-      f = ldf(fc + c);
+  for (int c0 = 0; c0 < d; c0 += kChunk(V)) {
+    Vec<V> f[kRegVecs], xv[kRegVecs];
+    if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, f);
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) {
+      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      if (c < d) {
+        if (ci < 0) f[it] = IO<T, V>::ld(fc + c);
+        xv[it] = ld_f32<V>(xr + c);
+      }
     }
-    const float v = xr[c] + f;
-    xr[c] = v;
-    ss += v * v;
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) {
+      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      if (c < d) {
+        if (ci >= 0) {
+#pragma unroll
+          for (int e = 0; e < V; ++e) f[it].v[e] = roundf_to<T>(f[it].v[e]);
+          IO<T, V>::st(fc + c, f[it]);
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          xv[it].v[e] += f[it].v[e];
+          ss += xv[it].v[e] * xv[it].v[e];
+        }
+        st_f32<V>(xr + c, xv[it]);
+        if (c0 == 0) keep[it] = xv[it];
+      }
+    }
   }
+  int it = 0;
   if (next_gain != nullptr) {
     ss = block_sum<kNW>(ss, red);
     const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
     T* hr = h + static_cast<size_t>(row) * d;
-    for (int c = threadIdx.x; c < d; c += kThreads) stf(hr + c, xr[c] * rstd * ldf(next_gain + c));
+    it = 0;
+    for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
+      Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
+      const Vec<V> g = IO<T, V>::ld(next_gain + c);
+#pragma unroll
+      for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * g.v[e];
+      IO<T, V>::st(hr + c, xv);
+    }
   } else {
     T* o = hidden_out + static_cast<size_t>(row) * d;
     const int pos = row % n;
     T* po = (prompt_out != nullptr && pos < L_p)
                 ? prompt_out + (static_cast<size_t>(row / n) * L_p + pos) * d
                 : nullptr;
-    for (int c = threadIdx.x; c < d; c += kThreads) {
-      const float v = xr[c];
-      stf(o + c, v);
-      if (po) stf(po + c, v);
+    it = 0;
+    for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
+      const Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
+      IO<T, V>::st(o + c, xv);
+      if (po) IO<T, V>::st(po + c, xv);
     }
   }
 }
@@ -240,32 +391,50 @@ __global__ void k_fill_sel_identity(int* sel, int L_r) {
   if (j < L_r) sel[static_cast<size_t>(blockIdx.y) * L_r + j] = j;
 }
 
+template <typename T> inline T* P(void* p) { return static_cast<T*>(p); }
+template <typename T> inline const T* P(const void* p) { return static_cast<const T*>(p); }
+
+inline bool vec_ok(int width, std::initializer_list<const void*> ptrs) {
+  if (width % 4) return false;
+  for (const void* p : ptrs)
+    if (p && (reinterpret_cast<uintptr_t>(p) & 15u)) return false;
+  return true;
+}
+
 }  // namespace
 
-template <typename T> static inline T* P(void* p) { return static_cast<T*>(p); }
-template <typename T> static inline const T* P(const void* p) { return static_cast<const T*>(p); }
+// launch KERNEL<T, 4> or KERNEL<T, 1> depending on whether 16-byte vectors apply
+#define DLLMC_ROW_LAUNCH(KERNEL, T, vec, grid, st, ...)                                      \
+  do {                                                                                       \
+    if (vec) hipLaunchKernelGGL((KERNEL<T, 4>), grid, dim3(kThreads), 0, st, __VA_ARGS__);    \
+    else hipLaunchKernelGGL((KERNEL<T, 1>), grid, dim3(kThreads), 0, st, __VA_ARGS__);        \
+  } while (0)
 
 void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int* rows, int M,
                        const void* gain, float* x, void* h, hipStream_t st) {
   if (M <= 0) return;
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_embed_norm<bf16_t>, dim3(M), dim3(kThreads), 0, st, P<bf16_t>(hidden_in),
-                       rows, a.d, a.eps, P<bf16_t>(gain), x, P<bf16_t>(h));
-  else
-    hipLaunchKernelGGL(k_embed_norm<float>, dim3(M), dim3(kThreads), 0, st, P<float>(hidden_in),
-                       rows, a.d, a.eps, P<float>(gain), x, P<float>(h));
+  const bool vec = vec_ok(a.d, {hidden_in, gain, x, h});
+  if (a.dtype == 1) {
+    DLLMC_ROW_LAUNCH(k_embed_norm, bf16_t, vec, dim3(M), st, P<bf16_t>(hidden_in), rows, a.d, a.eps,
+                     P<bf16_t>(gain), x, P<bf16_t>(h));
+  } else {
+    DLLMC_ROW_LAUNCH(k_embed_norm, float, vec, dim3(M), st, P<float>(hidden_in), rows, a.d, a.eps,
+                     P<float>(gain), x, P<float>(h));
+  }
 }
 
 void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                        int d_kv, void* v_cache, float* score, hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * d_kv;
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_v_finalize<bf16_t>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
-                       d_kv, a.n, a.L_p, P<bf16_t>(v_cache), score);
-  else
-    hipLaunchKernelGGL(k_v_finalize<float>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
-                       d_kv, a.n, a.L_p, P<float>(v_cache), score);
+  const bool vec = vec_ok(d_kv, {c_part, v_cache});
+  if (a.dtype == 1) {
+    DLLMC_ROW_LAUNCH(k_v_finalize, bf16_t, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
+                     P<bf16_t>(v_cache), score);
+  } else {
+    DLLMC_ROW_LAUNCH(k_v_finalize, float, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
+                     P<float>(v_cache), score);
+  }
 }
 
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
@@ -273,12 +442,13 @@ void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, cons
                         void* k_cache, hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * (d_q + d_kv);
+  const dim3 grid(M, (d_q + d_kv) / d_h);
   if (a.dtype == 1)
-    hipLaunchKernelGGL(k_qk_finalize<bf16_t>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride,
-                       rows, a.n, d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache));
+    hipLaunchKernelGGL(k_qk_finalize<bf16_t>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
+                       d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache));
   else
-    hipLaunchKernelGGL(k_qk_finalize<float>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride,
-                       rows, a.n, d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache));
+    hipLaunchKernelGGL(k_qk_finalize<float>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
+                       d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache));
 }
 
 void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
@@ -286,14 +456,14 @@ void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M
                        const void* gain, void* g_out, hipStream_t st) {
   if (Mc <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_o_finalize<bf16_t>, dim3(Mc), dim3(kThreads), 0, st, c_part, S, stride,
-                       carried, inv, a.d, a.eps, P<bf16_t>(attn_cache), x, P<bf16_t>(gain),
-                       P<bf16_t>(g_out));
-  else
-    hipLaunchKernelGGL(k_o_finalize<float>, dim3(Mc), dim3(kThreads), 0, st, c_part, S, stride,
-                       carried, inv, a.d, a.eps, P<float>(attn_cache), x, P<float>(gain),
-                       P<float>(g_out));
+  const bool vec = vec_ok(a.d, {c_part, attn_cache, x, gain, g_out});
+  if (a.dtype == 1) {
+    DLLMC_ROW_LAUNCH(k_o_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d, a.eps,
+                     P<bf16_t>(attn_cache), x, P<bf16_t>(gain), P<bf16_t>(g_out));
+  } else {
+    DLLMC_ROW_LAUNCH(k_o_finalize, float, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d, a.eps,
+                     P<float>(attn_cache), x, P<float>(gain), P<float>(g_out));
+  }
 }
 
 void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st) {
@@ -314,15 +484,16 @@ void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, in
                           hipStream_t st) {
   if (Mc <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_down_finalize<bf16_t>, dim3(Mc), dim3(kThreads), 0, st, c_part, S, stride,
-                       carried, inv, a.d, a.n, a.L_p, a.eps, P<bf16_t>(ffn_cache), x,
-                       P<bf16_t>(next_gain), P<bf16_t>(h), P<bf16_t>(hidden_out),
-                       P<bf16_t>(prompt_out));
-  else
-    hipLaunchKernelGGL(k_down_finalize<float>, dim3(Mc), dim3(kThreads), 0, st, c_part, S, stride,
-                       carried, inv, a.d, a.n, a.L_p, a.eps, P<float>(ffn_cache), x,
-                       P<float>(next_gain), P<float>(h), P<float>(hidden_out), P<float>(prompt_out));
+  const bool vec = vec_ok(a.d, {c_part, ffn_cache, x, next_gain, h, hidden_out, prompt_out});
+  if (a.dtype == 1) {
+    DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
+                     a.n, a.L_p, a.eps, P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
+                     P<bf16_t>(hidden_out), P<bf16_t>(prompt_out));
+  } else {
+    DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
+                     a.n, a.L_p, a.eps, P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
+                     P<float>(hidden_out), P<float>(prompt_out));
+  }
 }
 
 void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, void* hidden_out,

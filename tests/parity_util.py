@@ -1,10 +1,19 @@
 """Shared machinery of the GPU parity tests: run the HIP library and the CPU oracle on the same
 seeded inputs and compare them step by step.
 
-Selection rule (per layer and sequence): the GPU's index set must equal the oracle's
-whenever the oracle's margin at the selection boundary (s_(k+1) - s_(k)) exceeds 1e-4.
-Otherwise any set that is a valid bottom-k up to near-ties of width 1e-4 is accepted and
-the oracle continues with the GPU's set, so that later layers are compared on equal terms.
+Selection rule (per layer and sequence):
+  * always, bit-exact: the GPU's index set is the bottom-k (ties to the lower index) of the
+    GPU's own scores -- the integer part of the decision;
+  * the GPU's scores agree with the oracle's to SCORE_TOL;
+  * the GPU's set equals the oracle's whenever the oracle's margin at the selection boundary
+    (s_(k+1) - s_(k)) exceeds gap_tol(cfg); otherwise any set that is a valid bottom-k up to
+    near-ties of that width is accepted and the oracle continues with the GPU's set, so that
+    later layers are compared on equal terms.
+gap_tol is 1e-4 for float32 models.  For bf16 models the two sides round the same tensors to
+bf16 but sum in different orders (float32 tiles vs float64), so now and then one element of a
+V row lands on the neighbouring bf16 value; one such last-bit difference moves a cosine score
+by up to 2^-8 |v_i| / |v| ~ 2^-8 / sqrt(d_kv).  The band allows two of them:
+max(1e-4, 2 * 2^-8 / sqrt(d_kv)), i.e. 1.2e-4 at d_kv = 4096.
 """
 from __future__ import annotations
 
@@ -18,6 +27,16 @@ from oracle import dllm_cache_oracle as O
 from paper_2506_06295_amd import binding, inputs as I
 
 GAP_TOL = 1e-4
+
+
+def gap_tol(cfg: I.Config) -> float:
+    if cfg.dtype == "f32":
+        return GAP_TOL
+    return max(GAP_TOL, 2.0 * 2.0 ** -8 / np.sqrt(cfg.d_kv))
+
+
+def score_tol(cfg: I.Config) -> float:
+    return 1e-5 if cfg.dtype == "f32" else 4.0 * 2.0 ** -8 / np.sqrt(cfg.d_kv) + 1e-4
 
 
 def oracle_model(cfg: I.Config) -> O.Model:
@@ -54,6 +73,7 @@ class ParityStats:
     followed: int = 0       # margin <= 1e-4, GPU chose another admissible set
     failed: int = 0         # decisive margin but different set, or inadmissible set
     worst_rel: float = 0.0
+    worst_score_dev: float = 0.0
     rel_per_step: List[float] = field(default_factory=list)
     gaps: List[float] = field(default_factory=list)
     failures: List[str] = field(default_factory=list)
@@ -69,13 +89,27 @@ def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParitySta
     torch.cuda.synchronize()
     sel = gpu.sel_idx[:, :, :n_sel].cpu().numpy().astype(np.int64)
     k = ora.k_sel
+    tol = gap_tol(cfg)
+    adaptive = n_sel != cfg.L_r or not (i % ora.K_r == 0)
+    gpu_scores = None
+    if adaptive and i % ora.K_r != 0:
+        gpu_scores = gpu.read_scores()
+        torch.cuda.synchronize()
+        gpu_scores = gpu_scores.cpu().numpy()
+        # integer part of the decision: exact bottom-k of the GPU's own scores
+        for l in range(cfg.T):
+            for b in range(cfg.B):
+                want = O.bottom_k(gpu_scores[l, b].astype(np.float64), k)
+                assert sel[l, b].tolist() == want.tolist(), f"step {i} layer {l} seq {b}: select kernel"
 
     def on_layer(l, b, s, own):
         got = sel[l, b]
         gap = O.boundary_gap(s, k)
         stats.gaps.append(gap)
+        if gpu_scores is not None:
+            stats.worst_score_dev = max(stats.worst_score_dev, float(np.max(np.abs(gpu_scores[l, b] - s))))
         same = got.tolist() == own.tolist()
-        if gap > GAP_TOL:
+        if gap > tol:
             if same:
                 stats.exact += 1
                 return None
@@ -84,7 +118,7 @@ def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParitySta
         elif same:
             stats.tied_same += 1
             return None
-        elif O.selection_is_admissible(s, k, got, GAP_TOL):
+        elif O.selection_is_admissible(s, k, got, tol):
             stats.followed += 1
         else:
             stats.failed += 1

@@ -39,7 +39,7 @@ def report(name, stats):
     q = np.quantile(g, [0.1, 0.5, 0.9]).tolist() if g.size else []
     print(f"\n[{name}] selection: exact={stats.exact} tied_same={stats.tied_same} "
           f"followed={stats.followed} failed={stats.failed}; gap quantiles 10/50/90%: {q}; "
-          f"worst rel err {stats.worst_rel:.3e}")
+          f"worst rel err {stats.worst_rel:.3e}; worst |s_gpu - s_oracle| {stats.worst_score_dev:.2e}")
 
 
 def test_toy_schedule_fp32():
@@ -59,6 +59,7 @@ def test_toy_stress_schedule_fp32_exact_indices():
     assert st.failed == 0, st.failures
     assert st.exact > 0          # decisive boundaries really occur and match bit-exactly
     assert st.worst_rel <= 1e-4
+    assert st.worst_score_dev <= PU.score_tol(cfg)
     gpu.close()
 
 
@@ -79,6 +80,7 @@ def test_bf16_stress_schedule_exact_indices(cfg):
     assert st.failed == 0, st.failures
     assert st.exact > 0
     assert st.worst_rel <= 2e-2
+    assert st.worst_score_dev <= PU.score_tol(cfg)
     gpu.close()
 
 
