@@ -167,10 +167,12 @@ int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_
 /* Bidirectional attention of Mq query rows per sequence over all n cached keys of that
  * sequence, no mask (complexity appendix: the 4*r^*n*d term).  q, out: device [B, Mq, H_q*d_h];
  * k_cache, v_cache: device [B, n, H_kv*d_h]; all in the model dtype.  Query head a reads
- * key/value head a / (H_q/H_kv). */
+ * key/value head a / (H_q/H_kv).  scratch: device memory of dllmc_op_attention_scratch_bytes()
+ * bytes, or NULL; with it, small query sets have their key range split over workgroups. */
+size_t dllmc_op_attention_scratch_bytes(void);
 int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, const void* k_cache,
                        const void* v_cache, int32_t n, int32_t H_q, int32_t H_kv, int32_t d_h,
-                       void* out, void* hip_stream);
+                       void* out, float* scratch, void* hip_stream);
 
 #ifdef __cplusplus
 }

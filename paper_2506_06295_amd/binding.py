@@ -25,7 +25,7 @@ EXPORTS = (
     "dllmc_read_cache", "dllmc_read_scores", "dllmc_destroy", "dllmc_strerror",
     "dllmc_last_hip_error", "dllmc_op_select", "dllmc_op_vverify", "dllmc_op_linear",
     "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
-    "dllmc_set_gemm_tuning",
+    "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes",
 )
 NUM_KERNEL_CLASSES = 9
 
@@ -92,7 +92,9 @@ def lib() -> C.CDLL:
         L.dllmc_op_attention.restype = C.c_int
         L.dllmc_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                         C.c_void_p, C.c_void_p]
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dllmc_op_attention_scratch_bytes.restype = C.c_size_t
+        L.dllmc_op_attention_scratch_bytes.argtypes = []
         L.dllmc_profile_enable.restype = C.c_int
         L.dllmc_profile_enable.argtypes = [C.c_void_p, C.c_int32]
         L.dllmc_profile_read.restype = C.c_int
@@ -242,11 +244,14 @@ def op_linear(dtype: str, a: torch.Tensor, w: torch.Tensor, row_idx: Optional[to
 
 
 def op_attention(dtype: str, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
-                 H_q: int, H_kv: int, d_h: int) -> torch.Tensor:
+                 H_q: int, H_kv: int, d_h: int, split_keys: bool = True) -> torch.Tensor:
     B, Mq, _ = q.shape
     n = k_cache.shape[1]
     out = torch.empty_like(q)
+    scratch = None
+    if split_keys:
+        scratch = torch.empty(lib().dllmc_op_attention_scratch_bytes(), dtype=torch.uint8, device="cuda")
     _check(lib().dllmc_op_attention(_DTYPES[dtype][0], q.data_ptr(), B, Mq, k_cache.data_ptr(),
                                     v_cache.data_ptr(), n, H_q, H_kv, d_h, out.data_ptr(),
-                                    _stream_handle()), "dllmc_op_attention")
+                                    _ptr(scratch), _stream_handle()), "dllmc_op_attention")
     return out

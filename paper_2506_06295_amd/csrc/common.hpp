@@ -145,9 +145,11 @@ void launch_select(const float* scores, int B, int L, int k, int* sel_out, int s
 // q, out: [B, Mq, H_q*d_h]; k_cache, v_cache: [B, n, H_kv*d_h].
 // The float32 / odd-head-width kernel keeps one row of n scores in LDS.
 bool attention_supported(int dtype, int d_h, int n);
+// scratch (may be null): attention_scratch_floats() floats for the split-key partial results.
+size_t attention_scratch_floats();
 void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cache,
                       const void* v_cache, int n, int H_q, int H_kv, int d_h, void* out,
-                      hipStream_t st);
+                      float* scratch, hipStream_t st);
 
 // Row lists: for b < B, t < count: ci = b*per_seq + off + t, row = b*n + first + t;
 // rows[ci] = row (if rows), inv[row] = ci (if inv).

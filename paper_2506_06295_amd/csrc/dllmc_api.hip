@@ -46,7 +46,7 @@ struct Layout {
   size_t esz;
   size_t cache_k, cache_v, cache_ao, cache_fo;  // per-layer strides inside their regions
   size_t off_k, off_v, off_ao, off_fo, off_prompt_out, off_x, off_h, off_q, off_a, off_g, off_u,
-      off_cws, off_scores, off_carried, off_rows, off_inv, off_rope, total;
+      off_cws, off_attn, off_scores, off_carried, off_rows, off_inv, off_rope, total;
 };
 
 Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
@@ -78,6 +78,8 @@ Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
   // GEMM output slices: S*tiles < 512 + tiles workgroup tiles of 64 x 128 floats
   const size_t cws_floats = align_up(rows, 64) * n_max + static_cast<size_t>(640) * 64 * 128;
   L.off_cws = take(cws_floats * sizeof(float));
+  // split-key attention partials: only small query sets are split (at most 8 ways)
+  L.off_attn = take(attention_scratch_floats() * sizeof(float));
   L.off_scores = take(T * B * L_r * sizeof(float));
   L.off_carried = take(rows * sizeof(int));
   L.off_rows = take(rows * sizeof(int));
@@ -306,7 +308,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
         // queries in and out once, every sequence's K and V once per group of query heads
         Timed t(c, DLLMC_KC_ATTENTION, (2.0 * M_R * d_q + 2.0 * B * n * d_kv) * esz,
                 4.0 * M_R * static_cast<double>(n) * d_q);
-        launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf, st);
+        launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf,
+                         c->at<float>(c->lay.off_attn), st);
       }
       {
         Timed t(c, DLLMC_KC_GEMM_O, gemm_bytes(M_R, d, d_q), gemm_flops(M_R, d, d_q));
@@ -475,15 +478,17 @@ int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_
   return DLLMC_OK;
 }
 
+size_t dllmc_op_attention_scratch_bytes(void) { return attention_scratch_floats() * sizeof(float); }
+
 int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, const void* k_cache,
                        const void* v_cache, int32_t n, int32_t H_q, int32_t H_kv, int32_t d_h,
-                       void* out, void* hip_stream) {
+                       void* out, float* scratch, void* hip_stream) {
   if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !q || !k_cache || !v_cache || !out || B < 1 ||
       Mq < 1 || n < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv || d_h < 1 ||
       !attention_supported(dtype, d_h, n))
     return DLLMC_EINVAL;
   (void)hipGetLastError();
-  launch_attention(dtype, q, B, Mq, k_cache, v_cache, n, H_q, H_kv, d_h, out,
+  launch_attention(dtype, q, B, Mq, k_cache, v_cache, n, H_q, H_kv, d_h, out, scratch,
                    static_cast<hipStream_t>(hip_stream));
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;

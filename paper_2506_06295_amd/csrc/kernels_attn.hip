@@ -12,10 +12,10 @@
 //                     keys of a 32-key block: exactly the B-operand layout of the second
 //                     product O^T = V^T * P^T, so probabilities never leave registers.  K rows
 //                     are read straight from global memory (64 contiguous bytes per lane);
-//                     V tiles are transposed once through LDS.  The four wavefronts of a
-//                     workgroup are arranged as QW query groups x KW key ranges: with few
-//                     queries (adaptive steps) the key range is split for parallelism and the
-//                     partial results are merged through LDS at the end.
+//                     V tiles are transposed once per workgroup through LDS and shared by
+//                     its four 16-query wavefronts.  With few queries (adaptive steps) the
+//                     key range is split over workgroups and k_attn_merge combines the
+//                     partial results in key-range order.
 #include "common.hpp"
 
 namespace dllmc {
@@ -69,83 +69,112 @@ __global__ __launch_bounds__(64) void k_attn_simple(const T* __restrict__ q, int
   }
 }
 
-constexpr int kDH = 128;     // head width of the MFMA kernel
+constexpr int kDH = 128;       // head width of the MFMA kernel
 constexpr int kVtStride = 40;  // 32 keys + 8 pad (bf16 elements) per transposed V row
+constexpr int kQT = 64;        // queries per workgroup: four wavefronts x 16
+constexpr int kMaxKeySplit = 8;
 
-template <int QW, int KW>
+// Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; blockIdx.z
+// enumerates (sequence, key range).  All four wavefronts walk the same 32-key blocks, so a V
+// tile is transposed through LDS once per workgroup.  K fragments and the next V tile are
+// fetched one block ahead.  With KS == 1 the normalised output is written; otherwise the
+// un-normalised partial (O, m, l) of this key range goes to `part` for k_attn_merge.
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q, int Mq,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
-                                                   int H_kv, bf16_t* __restrict__ out) {
-  static_assert(QW * KW == 4, "four wavefronts per workgroup");
-  constexpr int QT = 16 * QW;  // queries per workgroup
-  // V^T tiles during the key loop, reused for the merge buffers afterwards
-  constexpr int kVtBytes = KW * kDH * kVtStride * 2;
-  constexpr int kMergeBytes = 4 * 16 * (kDH + 2) * 4;
-  constexpr int kSmem = kVtBytes > kMergeBytes ? kVtBytes : kMergeBytes;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[kSmem];
-
+                                                   int H_kv, int KS, bf16_t* __restrict__ out,
+                                                   float* __restrict__ part) {
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][kDH * kVtStride];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int qw = wave % QW, kw = wave / QW;
-  const int a = blockIdx.y, b = blockIdx.z;
+  const int a = blockIdx.y;
+  const int b = blockIdx.z / KS, ks = blockIdx.z % KS;
   const int d_q = H_q * kDH, d_kv = H_kv * kDH;
   const int kv = a / (H_q / H_kv);
-  const int i0 = blockIdx.x * QT;  // first query of this workgroup inside the sequence
+  const int i0 = blockIdx.x * kQT + wave * 16;  // first query of this wavefront
 
   const bf16_t* K = kc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
   const bf16_t* V = vc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
 
-  // Q fragments (B operand of S^T = K Q^T): lane (n = query ln, g = lg) holds dims 32g+8c..+8
-  int qi = i0 + qw * 16 + ln;
-  if (qi >= Mq) qi = Mq - 1;  // clamp: padded queries compute a duplicate that is never stored
-  const bf16_t* qr = q + (static_cast<size_t>(b) * Mq + qi) * d_q + a * kDH + lg * 32;
+  // Q fragments (B operand of S^T = K Q^T): lane (query ln, group lg) holds dims 32c+8lg..+8
+  int qi = i0 + ln;
+  if (qi >= Mq) qi = Mq - 1;  // padded queries compute a duplicate that is never stored
+  const bf16_t* qr = q + (static_cast<size_t>(b) * Mq + qi) * d_q + a * kDH + lg * 8;
   bf16x8 qf[4];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) qf[c] = *reinterpret_cast<const bf16x8*>(qr + c * 8);
+  for (int c = 0; c < 4; ++c) qf[c] = *reinterpret_cast<const bf16x8*>(qr + c * 32);
 
   const float sl2e = 1.4426950408889634f / sqrtf(static_cast<float>(kDH));  // scale * log2(e)
-  float m_run = -INFINITY;  // running maximum of the scaled scores (base-2 units), per query
+  float m_run = -INFINITY;  // running maximum of the scaled scores (base 2), per query
   float l_run = 0.f;        // this lane's share of the running denominator
   f32x4 o_acc[8];           // O^T: dims db*16 + 4*lg + i, query ln
 #pragma unroll
   for (int db = 0; db < 8; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int nblk = (n + 31) / 32;
-  const int per = (nblk + KW - 1) / KW;  // 32-key blocks per key range (same trip count for all)
-  bf16_t* Vt = reinterpret_cast<bf16_t*>(smem) + kw * kDH * kVtStride;
-  const int gtid = qw * 64 + lane;  // thread index inside this key range's group
+  const int per = (nblk + KS - 1) / KS;
+  const int blk0 = ks * per;
+  const int blk1 = min(nblk, blk0 + per);
 
-  for (int it = 0; it < per; ++it) {
-    const int kb = kw * per + it;
-    const int key0 = kb * 32;
-    __syncthreads();
-    // stage V[key0 .. key0+32) transposed: Vt[dim][key]
-    for (int e = gtid; e < 32 * 16; e += 64 * QW) {
-      const int key = e / 16, c = e % 16;
-      int kr = key0 + key;
+  // staging assignment: 32 keys x 16 chunks of 8 dims = 512 chunks, two per thread
+  const int skey = threadIdx.x / 16, sc = threadIdx.x % 16;  // keys skey and skey + 16
+  auto load_v = [&](int blk, uint4 (&raw)[2]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      int kr = blk * 32 + skey + 16 * h;
       if (kr >= n) kr = n - 1;  // masked below; any finite value will do
-      const uint4 raw = *reinterpret_cast<const uint4*>(V + static_cast<size_t>(kr) * d_kv + c * 8);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+      raw[h] = *reinterpret_cast<const uint4*>(V + static_cast<size_t>(kr) * d_kv + sc * 8);
+    }
+  };
+  auto store_v = [&](bf16_t* dst, const uint4 (&raw)[2]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t w[4] = {raw[h].x, raw[h].y, raw[h].z, raw[h].w};
+      const int key = skey + 16 * h;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        Vt[(c * 8 + 2 * j) * kVtStride + key] = static_cast<bf16_t>(w[j] & 0xffffu);
-        Vt[(c * 8 + 2 * j + 1) * kVtStride + key] = static_cast<bf16_t>(w[j] >> 16);
+        dst[(sc * 8 + 2 * j) * kVtStride + key] = static_cast<bf16_t>(w[j] & 0xffffu);
+        dst[(sc * 8 + 2 * j + 1) * kVtStride + key] = static_cast<bf16_t>(w[j] >> 16);
       }
     }
+  };
+  auto load_k = [&](int blk, bf16x8 (&kf)[2][4]) {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      int kr = blk * 32 + sb * 16 + ln;
+      if (kr >= n) kr = n - 1;
+      const bf16_t* kp = K + static_cast<size_t>(kr) * d_kv + lg * 8;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) kf[sb][c] = *reinterpret_cast<const bf16x8*>(kp + c * 32);
+    }
+  };
+
+  uint4 vraw[2];
+  bf16x8 kf[2][4];
+  if (blk0 < blk1) {
+    load_v(blk0, vraw);
+    load_k(blk0, kf);
+    store_v(Vt[0], vraw);
+  }
+  __syncthreads();
+
+  for (int blk = blk0; blk < blk1; ++blk) {
+    const int cur = (blk - blk0) & 1;
+    const bool more = blk + 1 < blk1;
+    bf16x8 kn[2][4];
+    if (more) {
+      load_v(blk + 1, vraw);
+      load_k(blk + 1, kn);
+    }
+    const int key0 = blk * 32;
     // scores of the two 16-key halves: S^T[key][query]
     f32x4 st[2];
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
-      int kr = key0 + sb * 16 + ln;
-      if (kr >= n) kr = n - 1;
-      const bf16_t* kp = K + static_cast<size_t>(kr) * d_kv + lg * 32;
       f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + c * 8);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[c], acc, 0, 0, 0);
-      }
+      for (int c = 0; c < 4; ++c)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sb][c], qf[c], acc, 0, 0, 0);
       st[sb] = acc;
     }
     // lane holds keys key0 + sb*16 + 4*lg + i of query ln
@@ -182,57 +211,87 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
       o_acc[db][2] *= alpha;
       o_acc[db][3] *= alpha;
     }
-    __syncthreads();
     // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
+    const bf16_t* vt = Vt[cur];
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
-      const bf16_t* vr = Vt + (db * 16 + ln) * kVtStride + 4 * lg;
+      const bf16_t* vr = vt + (db * 16 + ln) * kVtStride + 4 * lg;
       const uint2 lo = *reinterpret_cast<const uint2*>(vr);
       const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
       const uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[db], 0, 0, 0);
+      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf,
+                                                          o_acc[db], 0, 0, 0);
     }
+    if (more) {
+      store_v(Vt[cur ^ 1], vraw);
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) kf[sb][c] = kn[sb][c];
+    }
+    __syncthreads();
   }
 
-  // merge the KW key ranges and normalise
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
-  __syncthreads();
-  float* mo = reinterpret_cast<float*>(smem);  // [4 waves][16 queries][kDH + 2]: O^T, then m, l
-  {
-    float* w = mo + (wave * 16 + ln) * (kDH + 2);
+  const int iq = i0 + ln;
+  if (iq >= Mq) return;
+  if (KS == 1) {
+    const float inv_l = 1.0f / l_run;
+    bf16_t* o = out + (static_cast<size_t>(b) * Mq + iq) * d_q + a * kDH;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      uint2 t;
+      t.x = static_cast<uint32_t>(f32_to_bf16(o_acc[db][0] * inv_l)) |
+            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][1] * inv_l)) << 16);
+      t.y = static_cast<uint32_t>(f32_to_bf16(o_acc[db][2] * inv_l)) |
+            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][3] * inv_l)) << 16);
+      *reinterpret_cast<uint2*>(o + db * 16 + 4 * lg) = t;
+    }
+  } else {
+    // part[((b*Mq + iq)*H_q + a)*KS + ks][kDH + 2]
+    float* w = part + ((static_cast<size_t>(b) * Mq + iq) * H_q + a) * KS * (kDH + 2) +
+               static_cast<size_t>(ks) * (kDH + 2);
 #pragma unroll
     for (int db = 0; db < 8; ++db)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[db * 16 + 4 * lg + i] = o_acc[db][i];
+      *reinterpret_cast<float4*>(w + db * 16 + 4 * lg) =
+          make_float4(o_acc[db][0], o_acc[db][1], o_acc[db][2], o_acc[db][3]);
     if (lg == 0) {
       w[kDH] = m_run;
       w[kDH + 1] = l_run;
     }
   }
-  __syncthreads();
-  for (int e = threadIdx.x; e < QT * kDH; e += 256) {
-    const int ql = e / kDH, dim = e % kDH;  // query inside the workgroup tile
-    const int qwi = ql / 16, qn = ql % 16;
-    const int iq = i0 + ql;
-    if (iq >= Mq) continue;
-    float M = -INFINITY;
-#pragma unroll
-    for (int r = 0; r < KW; ++r) M = fmaxf(M, mo[((r * QW + qwi) * 16 + qn) * (kDH + 2) + kDH]);
-    float L = 0.f, O = 0.f;
-#pragma unroll
-    for (int r = 0; r < KW; ++r) {
-      const float* w = mo + ((r * QW + qwi) * 16 + qn) * (kDH + 2);
-      const float f = w[kDH] == -INFINITY ? 0.f : exp2f(w[kDH] - M);
-      L += w[kDH + 1] * f;
-      O += w[dim] * f;
-    }
-    out[(static_cast<size_t>(b) * Mq + iq) * d_q + a * kDH + dim] = f32_to_bf16(O / L);
+}
+
+// out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.
+// One wavefront per (query, head), two dims per lane.
+__global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ part, int KS, int H_q,
+                                                   bf16_t* __restrict__ out) {
+  const size_t qh = static_cast<size_t>(blockIdx.x);  // (b*Mq + iq)*H_q + a
+  const float* w = part + qh * KS * (kDH + 2);
+  float M = -INFINITY;
+  for (int r = 0; r < KS; ++r) M = fmaxf(M, w[r * (kDH + 2) + kDH]);
+  float L = 0.f, o0 = 0.f, o1 = 0.f;
+  const int dim = threadIdx.x * 2;
+  for (int r = 0; r < KS; ++r) {
+    const float* wr = w + r * (kDH + 2);
+    const float mr = wr[kDH];
+    const float f = mr == -INFINITY ? 0.f : exp2f(mr - M);
+    L += wr[kDH + 1] * f;
+    const float2 o = *reinterpret_cast<const float2*>(wr + dim);
+    o0 += o.x * f;
+    o1 += o.y * f;
   }
+  const uint32_t t = static_cast<uint32_t>(f32_to_bf16(o0 / L)) |
+                     (static_cast<uint32_t>(f32_to_bf16(o1 / L)) << 16);
+  *reinterpret_cast<uint32_t*>(out + qh * kDH + dim) = t;
 }
 
 }  // namespace
+
+// Keys are split only while (workgroups without split) * KS stays below 1024, and a workgroup
+// covers kQT (query, head) pairs per key range, so this bounds the partial results.
+size_t attention_scratch_floats() { return static_cast<size_t>(kQT) * 1024 * (kDH + 2); }
 
 bool attention_supported(int dtype, int d_h, int n) {
   if (dtype == 1 && d_h == kDH) return true;
@@ -241,20 +300,26 @@ bool attention_supported(int dtype, int d_h, int n) {
 
 void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cache,
                       const void* v_cache, int n, int H_q, int H_kv, int d_h, void* out,
-                      hipStream_t st) {
+                      float* scratch, hipStream_t st) {
   if (B <= 0 || Mq <= 0 || n <= 0) return;
   if (dtype == 1 && d_h == kDH) {
     const bf16_t* qq = static_cast<const bf16_t*>(q);
     const bf16_t* kk = static_cast<const bf16_t*>(k_cache);
     const bf16_t* vv = static_cast<const bf16_t*>(v_cache);
     bf16_t* oo = static_cast<bf16_t*>(out);
-    if (static_cast<long>(B) * ((Mq + 63) / 64) * H_q >= 256) {
-      hipLaunchKernelGGL((k_attn_mfma<4, 1>), dim3((Mq + 63) / 64, H_q, B), dim3(256), 0, st, qq, Mq,
-                         kk, vv, n, H_q, H_kv, oo);
-    } else {
-      hipLaunchKernelGGL((k_attn_mfma<1, 4>), dim3((Mq + 15) / 16, H_q, B), dim3(256), 0, st, qq, Mq,
-                         kk, vv, n, H_q, H_kv, oo);
+    const int qt = (Mq + kQT - 1) / kQT;
+    const int base = B * qt * H_q;  // workgroups without splitting the keys
+    const int nblk = (n + 31) / 32;
+    int KS = 1;
+    if (scratch != nullptr && base < 512) {
+      KS = (512 + base - 1) / base;
+      if (KS > kMaxKeySplit) KS = kMaxKeySplit;
+      if (KS > nblk / 2) KS = nblk / 2 > 0 ? nblk / 2 : 1;  // at least two blocks per range
     }
+    hipLaunchKernelGGL(k_attn_mfma, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
+                       H_kv, KS, oo, scratch);
+    if (KS > 1)
+      hipLaunchKernelGGL(k_attn_merge, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, H_q, oo);
     return;
   }
   const size_t lds = static_cast<size_t>(d_h + n) * sizeof(float);

@@ -161,14 +161,16 @@ def test_vverify_scores_and_cache_overwrite(dtype, rows, d, d_kv):
     ("bf16", 1, 7, 5, 2, 2, 128),        # fewer keys than one block
     ("bf16", 1, 9, 70, 2, 1, 64),        # head width without an MFMA kernel
 ])
-def test_attention_matches_oracle(dtype, B, Mq, n, H_q, H_kv, d_h):
+@pytest.mark.parametrize("split_keys", [True, False])
+def test_attention_matches_oracle(dtype, B, Mq, n, H_q, H_kv, d_h, split_keys):
     r = np.random.default_rng(Mq * 7 + n)
     q = r.standard_normal((B, Mq, H_q * d_h)).astype(np.float32)
     k = r.standard_normal((B, n, H_kv * d_h)).astype(np.float32)
     v = r.standard_normal((B, n, H_kv * d_h)).astype(np.float32)
     # make the softmax peaky for some queries and flat for others
     q[:, ::3] *= 0.05
-    got = binding.op_attention(dtype, dev(q, dtype), dev(k, dtype), dev(v, dtype), H_q, H_kv, d_h)
+    got = binding.op_attention(dtype, dev(q, dtype), dev(k, dtype), dev(v, dtype), H_q, H_kv, d_h,
+                               split_keys=split_keys)
     torch.cuda.synchronize()
     got = got.float().cpu().numpy()
     for b in range(B):
