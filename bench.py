@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-uncached", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--tune", default="", help="GEMM tuning knobs, e.g. nw=8,nw_dual=4,force_s=0,target_wg=256")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (sequences would shard across GPUs "
@@ -100,6 +101,8 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     cfg = I.CONFIGS[args.config]
+    if args.tune:
+        binding.set_gemm_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     K = args.steps if args.steps is not None else cfg.steps
     W = args.warmup if args.warmup is not None else cfg.steps
 

@@ -139,9 +139,12 @@ int dllmc_last_hip_error(void);
 /* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
  * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
  * of the fused gate/up kernel, force_s number of contraction slices (0 = automatic), target_wg
- * workgroups the automatic choice aims for.  Results are bit-reproducible for fixed settings;
- * different settings change the float32 summation order only. */
-int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg);
+ * workgroups the automatic choice aims for, tile_min_m number of activation rows from which
+ * the 128 x 128 tile kernel replaces the weight-streaming kernel.  Results are
+ * bit-reproducible for fixed settings; different settings change the float32 summation order
+ * only. */
+int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
+                          int32_t tile_min_m);
 
 /* ---- single operations of the step, exposed for unit parity tests and micro-benchmarks ---- */
 

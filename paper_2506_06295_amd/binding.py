@@ -102,7 +102,7 @@ def lib() -> C.CDLL:
         L.dllmc_kernel_class_name.restype = C.c_char_p
         L.dllmc_kernel_class_name.argtypes = [C.c_int32]
         L.dllmc_set_gemm_tuning.restype = C.c_int
-        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 4
+        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 5
         _lib = L
     return _lib
 
@@ -207,8 +207,10 @@ class CachedDenoiser:
             pass
 
 
-def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1) -> None:
-    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg), "dllmc_set_gemm_tuning")
+def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1,
+                    tile_min_m: int = -1) -> None:
+    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg, tile_min_m),
+           "dllmc_set_gemm_tuning")
 
 
 def op_select(scores: torch.Tensor, k: int) -> torch.Tensor:

@@ -71,6 +71,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // gemm_max_slices() * M * N floats.
 int gemm_max_slices();
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg);
+void gemm_set_tile_min_m(int m);
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
                 const void* W1, int N0, int N, int K, float* c_part, hipStream_t st);
 

@@ -75,8 +75,9 @@ Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
   size_t n_max = 2 * mf;
   if (d_q + d_kv > n_max) n_max = d_q + d_kv;
   if (d > n_max) n_max = d;
-  // GEMM output slices: S*tiles < 512 + tiles workgroup tiles of 64 x 128 floats
-  const size_t cws_floats = align_up(rows, 64) * n_max + static_cast<size_t>(640) * 64 * 128;
+  // GEMM output slices: the slice count S is chosen so that S*tiles < 512 + tiles workgroup
+  // tiles (of at most 128 x 128 floats), and S*M*N <= S*tiles*tile
+  const size_t cws_floats = align_up(rows, 128) * n_max + static_cast<size_t>(640) * 128 * 128;
   L.off_cws = take(cws_floats * sizeof(float));
   // split-key attention partials: only small query sets are split (at most 8 ways)
   L.off_attn = take(attention_scratch_floats() * sizeof(float));
@@ -434,8 +435,10 @@ const char* dllmc_strerror(int code) {
 
 int dllmc_last_hip_error(void) { return g_last_hip_error; }
 
-int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg) {
+int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
+                          int32_t tile_min_m) {
   gemm_set_tuning(nw, nw_dual, force_s, target_wg);
+  gemm_set_tile_min_m(tile_min_m);
   return DLLMC_OK;
 }
 

@@ -229,6 +229,118 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   }
 }
 
+// ------------------------------------------------------------------------------------
+// k_gemm_tile: bf16 MFMA kernel for many activation rows (refresh steps, V projection of all
+// response rows, batched sequences), where the work is bound by the matrix cores rather than
+// by the weight stream.  Workgroup = 4 wavefronts (2 x 2), tile = 128 rows x 128 columns,
+// each wavefront 64 x 64 as 4 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands
+// go through LDS in 64-wide steps of the contraction index; the next step's tiles are
+// fetched into registers while the current one is multiplied (one barrier per step).
+// blockIdx.z selects a slice of the contraction index; float32 partial sums go to slice z of C.
+constexpr int kTileM = 128, kTileN = 128, kTileK = 64, kTileLS = kTileK + 8;
+
+__global__ __launch_bounds__(256) void k_gemm_tile(const bf16_t* __restrict__ A, int lda,
+                                                   const int* __restrict__ rows, int M,
+                                                   const bf16_t* __restrict__ W0,
+                                                   const bf16_t* __restrict__ W1, int N0, int N,
+                                                   int K, int k_per_slice, float* __restrict__ C) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][kTileM * kTileLS];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][kTileN * kTileLS];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int wm = wave / 2, wn = wave % 2;  // wavefront position inside the tile
+  const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
+  const int kbeg = blockIdx.z * k_per_slice;
+  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kTileK
+  const int nkt = klen / kTileK;
+
+  // staging: 128 rows x 8 chunks of 16 bytes per operand and step, four chunks per thread
+  const bf16_t* asrc[4];
+  const bf16_t* bsrc[4];
+  int dst[4];
+  bool aval[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int e = threadIdx.x + j * 256;
+    const int r = e / 8, c = e % 8;
+    const int m = m0 + r;
+    aval[j] = m < M;
+    const int row = aval[j] ? (rows ? rows[m] : m) : 0;
+    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + c * 8;
+    const int nn = n0 + r;  // < N: N % 128 == 0
+    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
+              kbeg + c * 8;
+    dst[j] = r * kTileLS + c * 8;
+  }
+  f32x4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 ra[4], rb[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    ra[j] = aval[j] ? *reinterpret_cast<const uint4*>(asrc[j]) : make_uint4(0u, 0u, 0u, 0u);
+    rb[j] = *reinterpret_cast<const uint4*>(bsrc[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    *reinterpret_cast<uint4*>(&As[0][dst[j]]) = ra[j];
+    *reinterpret_cast<uint4*>(&Bs[0][dst[j]]) = rb[j];
+  }
+  __syncthreads();
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const bool more = kt + 1 < nkt;
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        ra[j] = aval[j] ? *reinterpret_cast<const uint4*>(asrc[j] + (kt + 1) * kTileK)
+                        : make_uint4(0u, 0u, 0u, 0u);
+        rb[j] = *reinterpret_cast<const uint4*>(bsrc[j] + (kt + 1) * kTileK);
+      }
+    }
+    const bf16_t* ap = &As[kt & 1][(wm * 64 + ln) * kTileLS + lg * 8];
+    const bf16_t* bp = &Bs[kt & 1][(wn * 64 + ln) * kTileLS + lg * 8];
+#pragma unroll
+    for (int ks = 0; ks < kTileK; ks += 32) {
+      bf16x8 af[4], bf[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        af[i] = *reinterpret_cast<const bf16x8*>(ap + i * 16 * kTileLS + ks);
+        bf[i] = *reinterpret_cast<const bf16x8*>(bp + i * 16 * kTileLS + ks);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        *reinterpret_cast<uint4*>(&As[(kt + 1) & 1][dst[j]]) = ra[j];
+        *reinterpret_cast<uint4*>(&Bs[(kt + 1) & 1][dst[j]]) = rb[j];
+      }
+    }
+    __syncthreads();
+  }
+
+  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int m = m0 + wm * 64 + i * 16 + lg * 4 + e;
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          Cs[static_cast<size_t>(m) * N + n0 + wn * 64 + j * 16 + ln] = acc[i][j][e];
+      }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
                                                        size_t MN, float* __restrict__ out) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -252,6 +364,8 @@ struct GemmTuning {
   int nw_dual = 4;     // same for the fused gate/up kernel
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
+  int tile_min_m = 1 << 30; // activation rows from which the 128 x 128 tile kernel is used
+                            // (off by default: the streaming kernel is faster at the sizes measured)
 } g_tune;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -269,6 +383,8 @@ bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const vo
          (W1 == nullptr || aligned16(W1));
 }
 }  // namespace
+
+void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
   if (nw == 4 || nw == 8) g_tune.nw = nw;
@@ -294,6 +410,19 @@ int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const
                          static_cast<const float*>(A), lda, rows, M, static_cast<const float*>(W0),
                          static_cast<const float*>(W1), N0, N, K, c_part);
     return 1;
+  }
+  if (M >= g_tune.tile_min_m && N % kTileN == 0 && N0 % kTileN == 0 && K % kTileK == 0) {
+    const int mt = (M + kTileM - 1) / kTileM, nt = N / kTileN;
+    int S = g_tune.force_s > 0 ? g_tune.force_s : (2 * g_tune.target_wg + mt * nt - 1) / (mt * nt);
+    S = S < 1 ? 1 : (S > kMaxSlices ? kMaxSlices : S);
+    int kps = ((K + S - 1) / S + kTileK - 1) / kTileK * kTileK;
+    if (kps < 4 * kTileK) kps = 4 * kTileK;
+    if (kps > K) kps = K;
+    S = (K + kps - 1) / kps;
+    hipLaunchKernelGGL(k_gemm_tile, dim3(nt, mt, S), dim3(256), 0, st,
+                       static_cast<const bf16_t*>(A), lda, rows, M, static_cast<const bf16_t*>(W0),
+                       static_cast<const bf16_t*>(W1), N0, N, K, kps, c_part);
+    return S;
   }
   const int KC = (K % 256 == 0) ? 256 : 128;
   const int mt = (M + 63) / 64, nt = N / BN;

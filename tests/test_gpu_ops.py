@@ -94,8 +94,24 @@ def test_select_rejects_bad_k():
     ("bf16", 20, 2432, 896, False),      # N = 19 * 128
     ("bf16", 40, 896, 2432, False),
     ("bf16", 17, 200, 72, True),         # falls back to the plain kernel
+    ("bf16", 256, 1024, 4096, True),     # 128 x 128 tile kernel, split contraction
+    ("bf16", 300, 512, 896, True),       # tile kernel, ragged last row tile, K = 14 * 64
+    ("bf16", 768, 2432, 1024, False),    # tile kernel, N = 19 * 128
 ])
 def test_linear_matches_matmul(dtype, M, N, K, gather):
+    run_linear_case(dtype, M, N, K, gather)
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 1024, 4096), (300, 512, 896), (768, 2432, 1024)])
+def test_linear_tile_kernel(M, N, K):
+    binding.set_gemm_tuning(tile_min_m=128)
+    try:
+        run_linear_case("bf16", M, N, K, True)
+    finally:
+        binding.set_gemm_tuning(tile_min_m=1 << 30)
+
+
+def run_linear_case(dtype, M, N, K, gather):
     r = np.random.default_rng(M + N + K)
     rows_total = M + 37
     a = r.standard_normal((rows_total, K)).astype(np.float32)
