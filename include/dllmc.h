@@ -109,8 +109,9 @@ int dllmc_read_cache(dllmc_ctx* ctx, int32_t layer, int32_t which, void* dst_dev
  * `dst_device`, float32 [n_layers, B, L_r]. */
 int dllmc_read_scores(dllmc_ctx* ctx, float* dst_device);
 
-/* Optional per-kernel timing.  While enabled, dllmc_step brackets each kernel launch with two
- * HIP events on the context's stream.  dllmc_profile_read waits for the stream, adds the
+/* Optional per-kernel timing.  While enabled, dllmc_step records one HIP event on the context's
+ * stream after every kernel launch (and one when the step starts); a kernel's time is the
+ * interval between the events before and after it, so it includes the dispatch gap.  dllmc_profile_read waits for the stream, adds the
  * elapsed times to running totals per kernel class and copies the totals to `out`
  * (DLLMC_NUM_KERNEL_CLASSES entries); reset != 0 clears the totals afterwards.  alg_bytes and
  * flops are the algorithmic figures of the launches (for a gathered linear map: weights and
@@ -118,6 +119,7 @@ int dllmc_read_scores(dllmc_ctx* ctx, float* dst_device);
 enum {
   DLLMC_KC_GEMM_V = 0, DLLMC_KC_GEMM_QK, DLLMC_KC_GEMM_O, DLLMC_KC_GEMM_GATE_UP,
   DLLMC_KC_GEMM_DOWN, DLLMC_KC_ATTENTION, DLLMC_KC_SELECT, DLLMC_KC_ROW, DLLMC_KC_LISTS,
+  DLLMC_KC_EVENT_OVERHEAD, /* an empty span per step: what one event record adds to a span */
   DLLMC_NUM_KERNEL_CLASSES
 };
 typedef struct {

@@ -108,6 +108,8 @@ struct dllmc_ctx {
   struct Span { hipEvent_t a, b; int cls; double bytes, flops; };
   std::vector<Span> spans;           // recorded, not yet read back
   std::vector<hipEvent_t> free_events;
+  std::vector<hipEvent_t> step_open_events;  // opening events of profiled steps, not yet recycled
+  hipEvent_t last_event = nullptr;           // event that closed the most recent span
   dllmc_kernel_stat totals[DLLMC_NUM_KERNEL_CLASSES] = {};
 
   hipEvent_t get_event() {
@@ -129,21 +131,21 @@ struct dllmc_ctx {
 };
 
 namespace {
-// Brackets the launches issued while it is alive with two events (only when profiling is on).
+// Times the launches issued while it is alive: the span runs from the event that closed the
+// previous span (or the step's opening event) to an event recorded when this object dies, so
+// consecutive kernels are separated by a single event and the spans of a step add up to the
+// step's duration.  Only active while profiling is on.
 struct Timed {
   dllmc_ctx* c;
-  hipEvent_t a = nullptr, b = nullptr;
   int cls; double bytes, flops;
-  Timed(dllmc_ctx* c_, int cls_, double bytes_, double flops_) : c(c_), cls(cls_), bytes(bytes_), flops(flops_) {
-    if (!c->profiling) return;
-    a = c->get_event();
-    b = c->get_event();
-    if (a && b) (void)hipEventRecord(a, c->st);
-  }
+  Timed(dllmc_ctx* c_, int cls_, double bytes_, double flops_) : c(c_), cls(cls_), bytes(bytes_), flops(flops_) {}
   ~Timed() {
-    if (!c->profiling || !a || !b) return;
+    if (!c->profiling || !c->last_event) return;
+    hipEvent_t b = c->get_event();
+    if (!b) return;
     (void)hipEventRecord(b, c->st);
-    c->spans.push_back({a, b, cls, bytes, flops});
+    c->spans.push_back({c->last_event, b, cls, bytes, flops});
+    c->last_event = b;
   }
 };
 }  // namespace
@@ -254,6 +256,15 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   void* prompt_out = c->ws + c->lay.off_prompt_out;
   const float2* rope_tab = c->at<float2>(c->lay.off_rope);
 
+  c->last_event = nullptr;
+  if (c->profiling) {
+    c->last_event = c->get_event();
+    if (c->last_event) {
+      (void)hipEventRecord(c->last_event, st);
+      c->step_open_events.push_back(c->last_event);
+      Timed empty(c, DLLMC_KC_EVENT_OVERHEAD, 0, 0);  // nothing launched inside this span
+    }
+  }
   const double esz = static_cast<double>(c->lay.esz);
   // algorithmic bytes / flops of one gathered linear map: weights, activations in, float32 out
   auto gemm_bytes = [&](double M, double N, double K) { return (N * K + M * K) * esz + M * N * 4.0; };
@@ -393,10 +404,12 @@ int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
     t.ms += ms;
     t.alg_bytes += sp.bytes;
     t.flops += sp.flops;
-    c->free_events.push_back(sp.a);
-    c->free_events.push_back(sp.b);
+    c->free_events.push_back(sp.b);  // sp.a is the previous span's b or a step's opening event
   }
   c->spans.clear();
+  for (hipEvent_t ev : c->step_open_events) c->free_events.push_back(ev);
+  c->step_open_events.clear();
+  c->last_event = nullptr;
   std::memcpy(out, c->totals, sizeof(c->totals));
   if (reset) std::memset(c->totals, 0, sizeof(c->totals));
   return DLLMC_OK;
@@ -405,17 +418,15 @@ int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
 const char* dllmc_kernel_class_name(int32_t cls) {
   static const char* names[DLLMC_NUM_KERNEL_CLASSES] = {
       "gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down", "attention", "select",
-      "row_kernels", "lists_and_copies"};
+      "row_kernels", "lists_and_copies", "event_overhead"};
   return (cls >= 0 && cls < DLLMC_NUM_KERNEL_CLASSES) ? names[cls] : "?";
 }
 
 int dllmc_destroy(dllmc_ctx* c) {
   if (!c) return DLLMC_EINVAL;
   hipError_t e = hipStreamSynchronize(c->st);  // the workspace goes back to the caller idle
-  for (const dllmc_ctx::Span& sp : c->spans) {
-    (void)hipEventDestroy(sp.a);
-    (void)hipEventDestroy(sp.b);
-  }
+  for (const dllmc_ctx::Span& sp : c->spans) (void)hipEventDestroy(sp.b);
+  for (hipEvent_t ev : c->step_open_events) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->free_events) (void)hipEventDestroy(ev);
   delete c;
   if (e != hipSuccess) return hip_fail(e);

@@ -21,6 +21,22 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 constexpr int kMaxSlices = 8;
+
+// Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest), and each XCD has
+// its own L2.  With several row tiles per column tile, remap (blockIdx.x, blockIdx.y) so that
+// all row tiles of one column tile run back to back on the same XCD: the weight tile is then
+// fetched from HBM once and the other row tiles hit in that XCD's L2.
+__device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
+  const int nt = gridDim.x, mt = gridDim.y;
+  col_tile = blockIdx.x;
+  row_tile = blockIdx.y;
+  if (mt > 1 && (nt & 7) == 0) {
+    const int lin = blockIdx.x + nt * blockIdx.y;
+    const int xcd = lin & 7, slot = lin >> 3;
+    row_tile = slot % mt;
+    col_tile = (slot / mt) * 8 + xcd;
+  }
+}
 int gemm_max_slices() { return kMaxSlices; }
 
 // ------------------------------------------------------------------------------------
@@ -115,11 +131,13 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   __shared__ __attribute__((aligned(16))) bf16_t As[2][64 * LS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int m0 = blockIdx.y * 64;
+  int col_tile, row_tile;
+  xcd_tile_map(col_tile, row_tile);
+  const int m0 = row_tile * 64;
   const int kbeg = blockIdx.z * k_per_slice;
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KC
   const int nph = klen / KC;
-  const int ncol = blockIdx.x * (16 * NW) + wave * 16 + ln;  // < N: N % (16*NW) == 0
+  const int ncol = col_tile * (16 * NW) + wave * 16 + ln;  // < N: N % (16*NW) == 0
   const bf16_t* wp[NB];
   if (DUAL) {
     wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + lg * 8;
@@ -249,7 +267,9 @@ __global__ __launch_bounds__(256) void k_gemm_tile(const bf16_t* __restrict__ A,
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int wm = wave / 2, wn = wave % 2;  // wavefront position inside the tile
-  const int m0 = blockIdx.y * kTileM, n0 = blockIdx.x * kTileN;
+  int col_tile, row_tile;
+  xcd_tile_map(col_tile, row_tile);
+  const int m0 = row_tile * kTileM, n0 = col_tile * kTileN;
   const int kbeg = blockIdx.z * k_per_slice;
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kTileK
   const int nkt = klen / kTileK;
