@@ -194,13 +194,17 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     const float m_new = fmaxf(m_run, mx);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
+    // probabilities as a bf16 pair (high part + remainder): the second product then carries
+    // ~16 bits of each probability instead of 8
     float psum = 0.f;
-    bf16x8 pf;
+    bf16x8 pf, pl;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float e = exp2f(p[t] - m_use);
       psum += e;
-      pf[t] = static_cast<__bf16>(e);
+      const __bf16 hi = static_cast<__bf16>(e);
+      pf[t] = hi;
+      pl[t] = static_cast<__bf16>(e - static_cast<float>(hi));
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -219,8 +223,9 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
       const uint2 lo = *reinterpret_cast<const uint2*>(vr);
       const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
       const uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), pf,
-                                                          o_acc[db], 0, 0, 0);
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[db], 0, 0, 0);
+      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o_acc[db], 0, 0, 0);
     }
     if (more) {
       store_v(Vt[cur ^ 1], vraw);

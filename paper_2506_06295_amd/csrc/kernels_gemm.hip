@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 // weight matrix).  The workgroup's slice of the contraction index is walked in phases of KC:
 // the activation tile of phase p+1 is fetched into registers while phase p is multiplied and
 // is written to the other LDS buffer at the end of the phase (one barrier per phase).  The
-// weight stream is prefetched one 128-wide step ahead and runs across phase boundaries.
+// weight stream is prefetched one whole phase ahead and runs across phase boundaries.
 // Lane (n = lane%16, g = lane/16) holds, for MFMA step c of a 128-wide step, the eight
 // weights W[col n][k0 + 32c + 8g ..+8]; the A operand is read from LDS at the same offsets.
 //   DUAL = 0: columns [0,N0) come from W0, [N0,N) from W1; float32 partial sums are stored
@@ -172,11 +172,16 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j]);
     *reinterpret_cast<uint4*>(&As[0][adst[j]]) = v;
   }
-  uint4 bn[NB][4];
+  // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
+  constexpr int NS = KC / 128;
+  uint4 bn[NB][NS][4];
 #pragma unroll
   for (int b = 0; b < NB; ++b)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) bn[b][c] = *reinterpret_cast<const uint4*>(wp[b] + c * 32);
+    for (int t = 0; t < NS; ++t)
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + t * 128 + c * 32);
   __syncthreads();
 
   for (int ph = 0; ph < nph; ++ph) {
@@ -191,25 +196,26 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     }
     const bf16_t* ap = &As[ph & 1][ln * LS + lg * 8];
 #pragma unroll
-    for (int ks = 0; ks < KC; ks += 128) {
+    for (int t = 0; t < NS; ++t) {
       uint4 bc[NB][4];
 #pragma unroll
       for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bc[b][c] = bn[b][c];
-      const int knext = ph * KC + ks + 128;
-      if (knext < klen) {
+        for (int c = 0; c < 4; ++c) bc[b][c] = bn[b][t][c];
+      if (more) {
+        const int knext = (ph + 1) * KC + t * 128;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            bn[b][c] = *reinterpret_cast<const uint4*>(wp[b] + knext + c * 32);
+            bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + knext + c * 32);
       }
 #pragma unroll
       for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-          const bf16x8 af = *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + ks + c * 32);
+          const bf16x8 af =
+              *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + t * 128 + c * 32);
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(

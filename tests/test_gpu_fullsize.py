@@ -1,0 +1,109 @@
+"""Parity at the headline workload's full size (LLaDA-8B shape: 32 layers, d 4096, L_p 512,
+L_r 256, bf16), in the launch configuration bench.py times: the first denoising steps of the
+schedule (a full refresh, then adaptive steps) on device-drawn random weights against the
+oracle, plus properties that hold at any size on the wider shapes (Dream-7B GQA widths, long
+prompt).  The oracle runs on the host cores; each test prints its progress.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dllm_cache_oracle as O
+from paper_2506_06295_amd import binding, inputs as I
+from tests import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+def make_gpu(cfg, weights, **over):
+    return binding.CachedDenoiser(
+        n_layers=cfg.T, d_model=cfg.d, n_q_heads=cfg.H_q, n_kv_heads=cfg.H_kv, head_dim=cfg.d_h,
+        d_ffn=cfg.m, batch=cfg.B, dtype=cfg.dtype, weights=weights, L_p=cfg.L_p, L_r=cfg.L_r,
+        rho=over.get("rho", cfg.rho), K_p=over.get("K_p", cfg.K_p), K_r=over.get("K_r", cfg.K_r),
+        rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+
+
+def test_llada8b_full_depth_first_steps_match_oracle():
+    cfg = I.CONFIGS["llada8b"]
+    t0 = time.time()
+    dev_w = I.device_weights(cfg)
+    host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]   # float32, 28 GB
+    print(f"\n[fullsize] weights ready {time.time() - t0:.1f}s", flush=True)
+    gpu = make_gpu(cfg, dev_w)
+    ora = O.CachedDenoiser(PU.oracle_model(cfg), host_w, cfg.B, cfg.L_p, cfg.L_r, cfg.rho, cfg.K_p,
+                           cfg.K_r, storage="bf16")
+    sched = I.TokenSchedule(cfg, stress=True)
+    stats = PU.ParityStats()
+    for i in range(3):
+        PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, stats)
+        print(f"[fullsize] step {i}: rel err {stats.rel_per_step[-1]:.3e}  t={time.time() - t0:.1f}s",
+              flush=True)
+    print(f"[fullsize] selection exact={stats.exact} tied_same={stats.tied_same} "
+          f"followed={stats.followed} failed={stats.failed}; worst |ds| {stats.worst_score_dev:.2e}",
+          flush=True)
+    assert stats.failed == 0, stats.failures
+    assert stats.exact > 0
+    assert stats.worst_rel <= 2e-2
+    assert stats.worst_score_dev <= PU.score_tol(cfg)
+    # sampled cache rows of the last layer
+    for which, name in ((0, "K"), (1, "V"), (2, "AttnOut"), (3, "FFNOut")):
+        got = gpu.read_cache(cfg.T - 1, which).float().cpu().numpy()
+        assert PU.rel_err(got, getattr(ora, name)[cfg.T - 1]) <= 2e-2, name
+    gpu.close()
+
+
+@pytest.mark.parametrize("name,layers", [("dream7b", 3), ("llada8b_long", 2)])
+def test_wide_shapes_properties_at_size(name, layers):
+    """Reduced depth, full width and length: refresh == uncached forward on the GPU itself,
+    bit-reproducibility, selection exactly the bottom-k of the GPU's scores, untouched rows."""
+    cfg = I.CONFIGS[name].replace(T=layers)
+    dev_w = I.device_weights(cfg)
+    tdt = torch.bfloat16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1234)
+    h0 = torch.randn((cfg.B, cfg.n, cfg.d), device="cuda", generator=g).to(tdt)
+    h1 = h0.clone()
+    rows = torch.randperm(cfg.L_r, device="cuda", generator=g)[: cfg.L_r // 3] + cfg.L_p
+    h1[:, rows] += 0.5 * torch.randn((cfg.B, rows.numel(), cfg.d), device="cuda", generator=g).to(tdt)
+
+    runs = []
+    for _ in range(2):
+        den = make_gpu(cfg, dev_w, K_p=8, K_r=8)
+        out0, _ = den.step(h0, 0)
+        out0 = out0.clone()
+        before = [den.read_cache(layers - 1, w).clone() for w in range(4)]
+        out1, n_sel = den.step(h1, 1)
+        torch.cuda.synchronize()
+        sel = den.sel_idx[:, :, :n_sel].clone()
+        scores = den.read_scores()
+        after = [den.read_cache(layers - 1, w) for w in range(4)]
+        torch.cuda.synchronize()
+        runs.append((out0, out1.clone(), sel, scores.clone()))
+        k = den.num_selected
+        assert n_sel == k == O.num_selected(cfg.rho, cfg.L_r)
+        for l in range(layers):
+            want = O.bottom_k(scores[l, 0].cpu().numpy().astype(np.float64), k)
+            assert sel[l, 0].cpu().numpy().tolist() == want.tolist()
+        rest = np.setdiff1d(np.arange(cfg.L_r), sel[layers - 1, 0].cpu().numpy()) + cfg.L_p
+        for w in (0, 2, 3):
+            assert torch.equal(after[w][0, rest], before[w][0, rest])
+            assert torch.equal(after[w][0, :cfg.L_p], before[w][0, :cfg.L_p])
+        den.close()
+    assert all(torch.equal(a, b) for a, b in zip(runs[0], runs[1]))
+
+    # a full-refresh step equals the uncached configuration (rho = 1, K_p = K_r = 1) bit for bit
+    unc = make_gpu(cfg, dev_w, rho=1.0, K_p=1, K_r=1)
+    u0, _ = unc.step(h0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(u0, runs[0][0])
+    # and against the oracle on sampled rows of the first layer's V cache
+    v_gpu = unc.read_cache(0, 1)[0].float().cpu().numpy()
+    w0 = {k: v.float().cpu().numpy().astype(np.float64) for k, v in dev_w[0].items()}
+    x = h0[0].float().cpu().numpy().astype(np.float64)
+    sample = np.random.default_rng(0).permutation(cfg.n)[:64]
+    hs = O.round_bf16(O.rmsnorm(x[sample], w0["attn_norm_g"], cfg.rms_eps))
+    v_ref = O.round_bf16(hs @ w0["wv"].T)
+    assert PU.rel_err(v_gpu[sample], v_ref) < 1e-3
+    unc.close()
