@@ -141,12 +141,20 @@ int dllmc_last_hip_error(void);
 /* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
  * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
  * of the fused gate/up kernel, force_s number of contraction slices (0 = automatic), target_wg
- * workgroups the automatic choice aims for, tile_min_m number of activation rows from which
- * the 128 x 128 tile kernel replaces the weight-streaming kernel.  Results are
+ * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
+ * from which the 128 x 128 tile kernel / the 256 x 256 LDS-direct kernel replaces the
+ * weight-streaming kernel.  Results are
  * bit-reproducible for fixed settings; different settings change the float32 summation order
  * only. */
 int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
-                          int32_t tile_min_m);
+                          int32_t tile_min_m, int32_t fat_min_m);
+
+/* Host-only: the number of contraction-index slices the library would use for a gathered
+ * linear map of M rows, N columns (the first N0 from one matrix), contraction length K, given a
+ * float32 slice buffer of capacity_floats elements and 16-byte aligned operands; 0 if M*N
+ * floats do not fit.  slices * M * N never exceeds capacity_floats. */
+int32_t dllmc_plan_gemm_slices(int32_t dtype, int32_t M, int32_t N, int32_t N0, int32_t K,
+                               size_t capacity_floats);
 
 /* ---- single operations of the step, exposed for unit parity tests and micro-benchmarks ---- */
 

@@ -25,7 +25,7 @@ EXPORTS = (
     "dllmc_read_cache", "dllmc_read_scores", "dllmc_destroy", "dllmc_strerror",
     "dllmc_last_hip_error", "dllmc_op_select", "dllmc_op_vverify", "dllmc_op_linear",
     "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
-    "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes",
+    "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
 )
 NUM_KERNEL_CLASSES = 10
 
@@ -101,8 +101,10 @@ def lib() -> C.CDLL:
         L.dllmc_profile_read.argtypes = [C.c_void_p, C.POINTER(dllmc_kernel_stat), C.c_int32]
         L.dllmc_kernel_class_name.restype = C.c_char_p
         L.dllmc_kernel_class_name.argtypes = [C.c_int32]
+        L.dllmc_plan_gemm_slices.restype = C.c_int32
+        L.dllmc_plan_gemm_slices.argtypes = [C.c_int32] * 5 + [C.c_size_t]
         L.dllmc_set_gemm_tuning.restype = C.c_int
-        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 5
+        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 6
         _lib = L
     return _lib
 
@@ -208,8 +210,8 @@ class CachedDenoiser:
 
 
 def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1,
-                    tile_min_m: int = -1) -> None:
-    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg, tile_min_m),
+                    tile_min_m: int = -1, fat_min_m: int = -1) -> None:
+    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg, tile_min_m, fat_min_m),
            "dllmc_set_gemm_tuning")
 
 

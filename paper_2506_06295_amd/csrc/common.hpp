@@ -67,13 +67,18 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // C_part[s][i][:] (float32, s < S) = partial products of A[rows[i], :] * [W0; W1]^T over the
 // s-th slice of the contraction index.  W0 holds output columns [0, N0), W1 columns [N0, N)
 // (W1 may be null when N0 == N).  rows == nullptr means the identity.  Returns the number
-// of slices S it used (>= 1) so that consumers sum c_part[0..S) in order; c_part must hold
-// gemm_max_slices() * M * N floats.
+// of slices S it used (>= 1) so that consumers sum c_part[0..S) in order.  c_part holds
+// c_capacity floats; S is chosen so that S * M * N fits, and 0 is returned (nothing launched)
+// if not even M * N floats fit.
 int gemm_max_slices();
+// slices launch_gemm would use for 16-byte aligned operands (0: capacity too small); host only
+int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity);
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg);
 void gemm_set_tile_min_m(int m);
+void gemm_set_fat_min_m(int m);
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
-                const void* W1, int N0, int N, int K, float* c_part, hipStream_t st);
+                const void* W1, int N0, int N, int K, float* c_part, size_t c_capacity,
+                hipStream_t st);
 
 // Fused gate/up projection with the SwiGLU product: u[i][j] = T(silu(a_i . w_gate_j) *
 // (a_i . w_up_j)), no slices, nothing but u written.  Returns false (and launches nothing)

@@ -44,6 +44,7 @@ bool model_ok(const dllmc_model* m, int L_p, int L_r) {
 // Carving of the caller's workspace.  Every region starts 256-byte aligned.
 struct Layout {
   size_t esz;
+  size_t cws_floats;  // capacity of the GEMM slice buffer
   size_t cache_k, cache_v, cache_ao, cache_fo;  // per-layer strides inside their regions
   size_t off_k, off_v, off_ao, off_fo, off_prompt_out, off_x, off_h, off_q, off_a, off_g, off_u,
       off_cws, off_attn, off_scores, off_carried, off_rows, off_inv, off_rope, total;
@@ -78,6 +79,7 @@ Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
   // GEMM output slices: the slice count S is chosen so that S*tiles < 512 + tiles workgroup
   // tiles (of at most 128 x 128 floats), and S*M*N <= S*tiles*tile
   const size_t cws_floats = align_up(rows, 128) * n_max + static_cast<size_t>(640) * 128 * 128;
+  L.cws_floats = cws_floats;
   L.off_cws = take(cws_floats * sizeof(float));
   // split-key attention partials: only small query sets are split (at most 8 ways)
   L.off_attn = take(attention_scratch_floats() * sizeof(float));
@@ -252,6 +254,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   void* gbuf = c->ws + c->lay.off_g;
   void* ubuf = c->ws + c->lay.off_u;
   float* cws = c->at<float>(c->lay.off_cws);
+  const size_t cws_cap = c->lay.cws_floats;
   float* scores = c->at<float>(c->lay.off_scores);
   void* prompt_out = c->ws + c->lay.off_prompt_out;
   const float2* rope_tab = c->at<float2>(c->lay.off_rope);
@@ -293,7 +296,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     int S;
     {
       Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
-      S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, st);
+      S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap, st);
+      if (S == 0) return DLLMC_ENOMEM;
     }
     float* sc = scores + static_cast<size_t>(l) * B * L_r;
     {
@@ -310,7 +314,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     if (M_R > 0) {
       {
         Timed t(c, DLLMC_KC_GEMM_QK, gemm_bytes(M_R, d_q + d_kv, d), gemm_flops(M_R, d_q + d_kv, d));
-        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, st);
+        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, cws_cap, st);
+        if (S == 0) return DLLMC_ENOMEM;
       }
       {
         Timed t(c, DLLMC_KC_ROW, M_R * (d_q + d_kv) * (4.0 + esz), 0);
@@ -325,7 +330,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       }
       {
         Timed t(c, DLLMC_KC_GEMM_O, gemm_bytes(M_R, d, d_q), gemm_flops(M_R, d, d_q));
-        S = launch_gemm(dt, abuf, d_q, nullptr, M_R, w.wo, nullptr, d, d, d_q, cws, st);
+        S = launch_gemm(dt, abuf, d_q, nullptr, M_R, w.wo, nullptr, d, d, d_q, cws, cws_cap, st);
+        if (S == 0) return DLLMC_ENOMEM;
       }
     }
     {
@@ -337,7 +343,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       {
         Timed t(c, DLLMC_KC_GEMM_GATE_UP, gemm_bytes(M_R, 2.0 * mf, d), gemm_flops(M_R, 2.0 * mf, d));
         fused = launch_gemm_swiglu(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, d, ubuf, st);
-        if (!fused) S = launch_gemm(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, 2 * mf, d, cws, st);
+        if (!fused) S = launch_gemm(dt, gbuf, d, nullptr, M_R, w.w_gate, w.w_up, mf, 2 * mf, d, cws, cws_cap, st);
+        if (S == 0) return DLLMC_ENOMEM;
       }
       if (!fused) {
         Timed t(c, DLLMC_KC_ROW, M_R * mf * (8.0 + esz), 0);
@@ -345,7 +352,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       }
       {
         Timed t(c, DLLMC_KC_GEMM_DOWN, gemm_bytes(M_R, d, mf), gemm_flops(M_R, d, mf));
-        S = launch_gemm(dt, ubuf, mf, nullptr, M_R, w.w_down, nullptr, d, d, mf, cws, st);
+        S = launch_gemm(dt, ubuf, mf, nullptr, M_R, w.w_down, nullptr, d, d, mf, cws, cws_cap, st);
+        if (S == 0) return DLLMC_ENOMEM;
       }
     }
     const bool last = (l == T - 1);
@@ -446,10 +454,16 @@ const char* dllmc_strerror(int code) {
 
 int dllmc_last_hip_error(void) { return g_last_hip_error; }
 
+int32_t dllmc_plan_gemm_slices(int32_t dtype, int32_t M, int32_t N, int32_t N0, int32_t K,
+                               size_t capacity_floats) {
+  return gemm_plan_slices(dtype, M, N, N0, K, capacity_floats);
+}
+
 int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
-                          int32_t tile_min_m) {
+                          int32_t tile_min_m, int32_t fat_min_m) {
   gemm_set_tuning(nw, nw_dual, force_s, target_wg);
   gemm_set_tile_min_m(tile_min_m);
+  gemm_set_fat_min_m(fat_min_m);
   return DLLMC_OK;
 }
 
@@ -472,7 +486,9 @@ int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache
     return DLLMC_EINVAL;
   (void)hipGetLastError();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int S = launch_gemm(dtype, h, d, nullptr, rows, wv, nullptr, d_kv, d_kv, d, scratch, st);
+  const int S = launch_gemm(dtype, h, d, nullptr, rows, wv, nullptr, d_kv, d_kv, d, scratch,
+                            static_cast<size_t>(rows) * d_kv * 8, st);
+  if (S == 0) return DLLMC_ENOMEM;
   const RowKernelArgs ra{dtype, rows, 0, d, 0.f};
   launch_v_finalize(ra, scratch, S, nullptr, rows, d_kv, v_cache, scores, st);
   HIP_TRY(hipGetLastError());
@@ -486,7 +502,9 @@ int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_
     return DLLMC_EINVAL;
   (void)hipGetLastError();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int S = launch_gemm(dtype, a, K, row_idx, M, w, nullptr, N, N, K, scratch, st);
+  const int S = launch_gemm(dtype, a, K, row_idx, M, w, nullptr, N, N, K, scratch,
+                            static_cast<size_t>(M) * N * 8, st);
+  if (S == 0) return DLLMC_ENOMEM;
   launch_reduce_slices(scratch, S, M, N, out, st);
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;

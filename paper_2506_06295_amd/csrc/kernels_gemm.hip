@@ -367,6 +367,119 @@ __global__ __launch_bounds__(256) void k_gemm_tile(const bf16_t* __restrict__ A,
     }
 }
 
+// ------------------------------------------------------------------------------------
+// k_gemm_fat: bf16 MFMA kernel for many activation rows with a 256 x 256 tile, so that every
+// byte pulled from L2 feeds 128 flops.  Workgroup = 8 wavefronts (2 x 4), each 128 rows x 64
+// columns = 8 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands reach LDS with
+// global_load_lds_dwordx4 (no VGPR staging): a wavefront instruction copies 8 rows x 128
+// contiguous bytes (64 values of the contraction index) into 1 KB of LDS in lane order, i.e.
+// LDS holds [row][8 slots of 16 bytes]; the slot of chunk c of row r is c ^ (r % 8) so that
+// the 16-byte fragment reads of 8 consecutive rows hit 8 different bank groups.  Two LDS
+// stages of 64 KB: the loads of step t+1 are in flight while step t is multiplied.
+// Rows beyond M read a valid row again and are dropped at the store.
+constexpr int kFatM = 256, kFatN = 256, kFatK = 64;
+
+__device__ __forceinline__ void wait_vmcnt(int n) {
+  // s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
+  if (n == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
+  else __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+}
+
+__global__ __launch_bounds__(512) void k_gemm_fat(const bf16_t* __restrict__ A, int lda,
+                                                  const int* __restrict__ rows, int M,
+                                                  const bf16_t* __restrict__ W0,
+                                                  const bf16_t* __restrict__ W1, int N0, int N,
+                                                  int K, int k_per_slice, float* __restrict__ C) {
+  // [stage][operand (0 = activations, 1 = weights)][row * 8 + slot], 16 bytes each
+  __shared__ __attribute__((aligned(1024))) uint4 lds[2][2][kFatM * 8];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int wm = wave / 4, wn = wave % 4;
+  int col_tile, row_tile;
+  xcd_tile_map(col_tile, row_tile);
+  const int m0 = row_tile * kFatM, n0 = col_tile * kFatN;
+  const int kbeg = blockIdx.z * k_per_slice;
+  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kFatK
+  const int nkt = klen / kFatK;
+
+  // loader: instruction q (0..31) of an operand covers rows [8q, 8q+8); wavefront w issues
+  // q = 4w .. 4w+3.  Lane l: row 8q + l/8, LDS slot l%8, global chunk (l%8) ^ (row%8).
+  const bf16_t* asrc[4];
+  const bf16_t* bsrc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = 8 * (4 * wave + j) + lane / 8;
+    const int chunk = (lane % 8) ^ (r % 8);
+    int m = m0 + r;
+    if (m >= M) m = M - 1;
+    const int row = rows ? rows[m] : m;
+    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + chunk * 8;
+    const int nn = n0 + r;  // < N: N % 256 == 0
+    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
+              kbeg + chunk * 8;
+  }
+  auto issue = [&](int stage, int kt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = 4 * wave + j;
+      __builtin_amdgcn_global_load_lds(asrc[j] + kt * kFatK, &lds[stage][0][q * 64], 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(bsrc[j] + kt * kFatK, &lds[stage][1][q * 64], 16, 0, 0);
+    }
+  };
+
+  f32x4 acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  issue(0, 0);
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < nkt;
+    if (more) issue(cur ^ 1, kt + 1);
+    wait_vmcnt(more ? 8 : 0);  // this wavefront's loads of step kt have landed
+    // bare barrier (no memory fence: a fence would wait for the loads of step kt+1 as well)
+    __builtin_amdgcn_s_barrier();  // ... and everybody else's
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int c = kk * 4 + lg;  // 16-byte chunk of the 64-wide step this lane group multiplies
+      bf16x8 af[8], bf[4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = wm * 128 + i * 16 + ln;
+        af[i] = __builtin_bit_cast(bf16x8, lds[cur][0][r * 8 + (c ^ (r % 8))]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = wn * 64 + j * 16 + ln;
+        bf[j] = __builtin_bit_cast(bf16x8, lds[cur][1][r * 8 + (c ^ (r % 8))]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    // all LDS reads of this stage are complete (their results fed the MFMAs above) before the
+    // loads issued in the next iteration overwrite it
+    __builtin_amdgcn_s_barrier();
+  }
+
+  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int m = m0 + wm * 128 + i * 16 + lg * 4 + e;
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          Cs[static_cast<size_t>(m) * N + n0 + wn * 64 + j * 16 + ln] = acc[i][j][e];
+      }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
                                                        size_t MN, float* __restrict__ out) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -390,6 +503,7 @@ struct GemmTuning {
   int nw_dual = 4;     // same for the fused gate/up kernel
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
+  int fat_min_m = 384;      // activation rows from which the 256 x 256 LDS-direct kernel is used
   int tile_min_m = 1 << 30; // activation rows from which the 128 x 128 tile kernel is used
                             // (off by default: the streaming kernel is faster at the sizes measured)
 } g_tune;
@@ -411,6 +525,7 @@ bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const vo
 }  // namespace
 
 void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
+void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
   if (nw == 4 || nw == 8) g_tune.nw = nw;
@@ -419,57 +534,126 @@ void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
   if (target_wg > 0) g_tune.target_wg = target_wg;
 }
 
-int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
-                const void* W1, int N0, int N, int K, float* c_part, hipStream_t st) {
-  if (M <= 0 || N <= 0) return 1;
+// Which kernel, how many slices of the contraction index and how long a slice: pure host logic.
+struct GemmPlan {
+  int kind;  // 0 nothing fits, 1 plain, 2 streaming, 3 256x256 LDS-direct, 4 128x128 tile
+  int S, kps, KC, nt, mt;
+};
+
+GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int N0, int K,
+                   size_t c_capacity) {
+  GemmPlan p{0, 0, 0, 0, 0, 0};
+  const size_t MN = static_cast<size_t>(M) * N;
+  if (M <= 0 || N <= 0 || K <= 0 || c_capacity < MN) return p;
+  // most slices the caller's buffer can hold
+  const int s_cap = static_cast<int>(c_capacity / MN < static_cast<size_t>(kMaxSlices)
+                                         ? c_capacity / MN : static_cast<size_t>(kMaxSlices));
   const int NW = g_tune.nw;
   const int BN = 16 * NW;
-  if (!(stream_shape_ok(dtype, A, lda, W0, W1, K) && N % BN == 0 && N0 % BN == 0)) {
-    dim3 grid((N + 63) / 64, (M + 63) / 64);
-    if (dtype == 1)
-      hipLaunchKernelGGL(k_gemm_simple<bf16_t>, grid, dim3(256), 0, st,
-                         static_cast<const bf16_t*>(A), lda, rows, M,
-                         static_cast<const bf16_t*>(W0), static_cast<const bf16_t*>(W1), N0, N, K,
-                         c_part);
-    else
-      hipLaunchKernelGGL(k_gemm_simple<float>, grid, dim3(256), 0, st,
-                         static_cast<const float*>(A), lda, rows, M, static_cast<const float*>(W0),
-                         static_cast<const float*>(W1), N0, N, K, c_part);
-    return 1;
+  const bool mfma_ok = dtype == 1 && operands_aligned && (K % 128 == 0) && (lda % 8 == 0);
+  if (!(mfma_ok && N % BN == 0 && N0 % BN == 0)) {
+    p.kind = 1; p.S = 1; p.kps = K; p.nt = (N + 63) / 64; p.mt = (M + 63) / 64;
+    return p;
+  }
+  if (M >= g_tune.fat_min_m && N % kFatN == 0 && N0 % kFatN == 0 && K % kFatK == 0) {
+    p.kind = 3;
+    p.mt = (M + kFatM - 1) / kFatM;
+    p.nt = N / kFatN;
+    // One workgroup per CU (128 KB of LDS).  Choose the slice count with the lowest estimated
+    // time: rounds of tiles over the 256 CUs at the measured ~1.1 PFLOP/s steady rate of this
+    // kernel, plus writing and re-reading the float32 partial sums at ~5 TB/s.
+    int S = 1;
+    if (g_tune.force_s > 0) {
+      S = g_tune.force_s;
+    } else {
+      double best = 1e30;
+      for (int sl = 1; sl <= s_cap; ++sl) {
+        if (K / sl < 8 * kFatK) break;
+        const int kslice = ((K + sl - 1) / sl + kFatK - 1) / kFatK * kFatK;
+        const int rounds = (p.mt * p.nt * sl + 255) / 256;
+        const double t_tile = 2.0 * kFatM * kFatN * kslice / (1.1e15 / 256.0);
+        const double t_part = sl > 1 ? 2.0 * sl * static_cast<double>(MN) * 4.0 / 5e12 : 0.0;
+        const double cost = rounds * t_tile + t_part;
+        if (cost < best * 0.98) { best = cost; S = sl; }
+      }
+    }
+    S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
+    p.kps = ((K + S - 1) / S + kFatK - 1) / kFatK * kFatK;
+    if (p.kps > K) p.kps = K;
+    p.S = (K + p.kps - 1) / p.kps;
+    return p;
   }
   if (M >= g_tune.tile_min_m && N % kTileN == 0 && N0 % kTileN == 0 && K % kTileK == 0) {
-    const int mt = (M + kTileM - 1) / kTileM, nt = N / kTileN;
-    int S = g_tune.force_s > 0 ? g_tune.force_s : (2 * g_tune.target_wg + mt * nt - 1) / (mt * nt);
-    S = S < 1 ? 1 : (S > kMaxSlices ? kMaxSlices : S);
-    int kps = ((K + S - 1) / S + kTileK - 1) / kTileK * kTileK;
-    if (kps < 4 * kTileK) kps = 4 * kTileK;
-    if (kps > K) kps = K;
-    S = (K + kps - 1) / kps;
-    hipLaunchKernelGGL(k_gemm_tile, dim3(nt, mt, S), dim3(256), 0, st,
-                       static_cast<const bf16_t*>(A), lda, rows, M, static_cast<const bf16_t*>(W0),
-                       static_cast<const bf16_t*>(W1), N0, N, K, kps, c_part);
-    return S;
+    p.kind = 4;
+    p.mt = (M + kTileM - 1) / kTileM;
+    p.nt = N / kTileN;
+    int S = g_tune.force_s > 0 ? g_tune.force_s
+                               : (2 * g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
+    S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
+    p.kps = ((K + S - 1) / S + kTileK - 1) / kTileK * kTileK;
+    if (p.kps < 4 * kTileK) p.kps = 4 * kTileK;
+    if (p.kps > K) p.kps = K;
+    p.S = (K + p.kps - 1) / p.kps;
+    return p;
   }
-  const int KC = (K % 256 == 0) ? 256 : 128;
-  const int mt = (M + 63) / 64, nt = N / BN;
-  int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + mt * nt - 1) / (mt * nt);
-  S = S < 1 ? 1 : (S > kMaxSlices ? kMaxSlices : S);
-  int kps = ((K + S - 1) / S + KC - 1) / KC * KC;
-  if (kps > K) kps = K;
-  S = (K + kps - 1) / kps;
-  const dim3 grid(nt, mt, S);
+  p.kind = 2;
+  p.KC = (K % 256 == 0) ? 256 : 128;
+  p.mt = (M + 63) / 64;
+  p.nt = N / BN;
+  int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
+  S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
+  p.kps = ((K + S - 1) / S + p.KC - 1) / p.KC * p.KC;
+  if (p.kps > K) p.kps = K;
+  p.S = (K + p.kps - 1) / p.kps;
+  return p;
+}
+
+int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity) {
+  return plan_gemm(dtype, true, K, M, N, N0, K, c_capacity).S;
+}
+
+int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
+                const void* W1, int N0, int N, int K, float* c_part, size_t c_capacity,
+                hipStream_t st) {
+  if (M <= 0 || N <= 0) return 1;
+  const bool al = aligned16(A) && aligned16(W0) && (W1 == nullptr || aligned16(W1));
+  const GemmPlan p = plan_gemm(dtype, al, lda, M, N, N0, K, c_capacity);
+  if (p.kind == 0 || static_cast<size_t>(p.S) * M * N > c_capacity) return 0;  // nothing launched
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(W0);
   const bf16_t* w1 = static_cast<const bf16_t*>(W1);
+  const dim3 grid(p.nt, p.mt, p.S);
+  switch (p.kind) {
+    case 1:
+      if (dtype == 1)
+        hipLaunchKernelGGL(k_gemm_simple<bf16_t>, grid, dim3(256), 0, st, a, lda, rows, M, w0, w1, N0,
+                           N, K, c_part);
+      else
+        hipLaunchKernelGGL(k_gemm_simple<float>, grid, dim3(256), 0, st,
+                           static_cast<const float*>(A), lda, rows, M,
+                           static_cast<const float*>(W0), static_cast<const float*>(W1), N0, N, K,
+                           c_part);
+      break;
+    case 3:
+      hipLaunchKernelGGL(k_gemm_fat, grid, dim3(512), 0, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps,
+                         c_part);
+      break;
+    case 4:
+      hipLaunchKernelGGL(k_gemm_tile, grid, dim3(256), 0, st, a, lda, rows, M, w0, w1, N0, N, K,
+                         p.kps, c_part);
+      break;
+    default: {
 #define DLLMC_GS(NWv, KCv) \
-  launch_stream<NWv, KCv, 0>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, kps, c_part, nullptr)
-  if (NW == 8) {
-    if (KC == 256) DLLMC_GS(8, 256); else DLLMC_GS(8, 128);
-  } else {
-    if (KC == 256) DLLMC_GS(4, 256); else DLLMC_GS(4, 128);
-  }
+  launch_stream<NWv, KCv, 0>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps, c_part, nullptr)
+      if (g_tune.nw == 8) {
+        if (p.KC == 256) DLLMC_GS(8, 256); else DLLMC_GS(8, 128);
+      } else {
+        if (p.KC == 256) DLLMC_GS(4, 256); else DLLMC_GS(4, 128);
+      }
 #undef DLLMC_GS
-  return S;
+    }
+  }
+  return p.S;
 }
 
 bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int M,

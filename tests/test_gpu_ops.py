@@ -111,6 +111,15 @@ def test_linear_tile_kernel(M, N, K):
         binding.set_gemm_tuning(tile_min_m=1 << 30)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 1024, 4096), (300, 512, 896), (768, 2304, 1024), (100, 256, 512)])
+def test_linear_fat_kernel(M, N, K):
+    binding.set_gemm_tuning(fat_min_m=64)
+    try:
+        run_linear_case("bf16", M, N, K, True)
+    finally:
+        binding.set_gemm_tuning(fat_min_m=384)
+
+
 def run_linear_case(dtype, M, N, K, gather):
     r = np.random.default_rng(M + N + K)
     rows_total = M + 37
