@@ -4,6 +4,8 @@ schedule (a full refresh, then adaptive steps) on device-drawn random weights ag
 oracle, plus properties that hold at any size on the wider shapes (Dream-7B GQA widths, long
 prompt).  The oracle runs on the host cores; each test prints its progress.
 """
+import json
+import os
 import time
 
 import numpy as np
@@ -25,8 +27,18 @@ def make_gpu(cfg, weights, **over):
         rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
 
 
+def noise_floor():
+    """How far two valid bf16 evaluations of this model are apart (oracle with float32 vs float64
+    accumulation; tests/golden/make_bf16_noise_floor.py): no implementation can be closer to the
+    oracle than that, so the bar at depth is max(2e-2, 1.25 x floor)."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bf16_noise_floor_llada8b.json")
+    return json.load(open(path))
+
+
 def test_llada8b_full_depth_first_steps_match_oracle():
     cfg = I.CONFIGS["llada8b"]
+    floor = noise_floor()
+    bar = lambda f: max(2e-2, 1.25 * f)
     t0 = time.time()
     dev_w = I.device_weights(cfg)
     host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]   # float32, 28 GB
@@ -45,16 +57,19 @@ def test_llada8b_full_depth_first_steps_match_oracle():
           flush=True)
     assert stats.failed == 0, stats.failures
     assert stats.exact > 0
-    assert stats.worst_rel <= 2e-2
+    assert stats.worst_rel <= bar(floor["hidden_out"])
     assert stats.worst_score_dev <= PU.score_tol(cfg)
-    # sampled cache rows of the last layer
-    for which, name in ((0, "K"), (1, "V"), (2, "AttnOut"), (3, "FFNOut")):
-        got = gpu.read_cache(cfg.T - 1, which).float().cpu().numpy()
-        assert PU.rel_err(got, getattr(ora, name)[cfg.T - 1]) <= 2e-2, name
+    # cache tensors of the first, a middle and the last layer
+    for l in (0, cfg.T // 2, cfg.T - 1):
+        for which, name in ((0, "K"), (1, "V"), (2, "AttnOut"), (3, "FFNOut")):
+            got = gpu.read_cache(l, which).float().cpu().numpy()
+            e = PU.rel_err(got, getattr(ora, name)[l])
+            print(f"[fullsize] layer {l} {name}: rel err {e:.3e} (floor {floor[f'layer{l}'][name]:.3e})", flush=True)
+            assert e <= bar(floor[f"layer{l}"][name]), (l, name, e)
     gpu.close()
 
 
-@pytest.mark.parametrize("name,layers", [("dream7b", 3), ("llada8b_long", 2)])
+@pytest.mark.parametrize("name,layers", [("dream7b", 3), ("llada8b_long", 2), ("llada8b_b16", 2)])
 def test_wide_shapes_properties_at_size(name, layers):
     """Reduced depth, full width and length: refresh == uncached forward on the GPU itself,
     bit-reproducibility, selection exactly the bottom-k of the GPU's scores, untouched rows."""
@@ -83,13 +98,15 @@ def test_wide_shapes_properties_at_size(name, layers):
         runs.append((out0, out1.clone(), sel, scores.clone()))
         k = den.num_selected
         assert n_sel == k == O.num_selected(cfg.rho, cfg.L_r)
+        sc_host, sel_host = scores.cpu().numpy().astype(np.float64), sel.cpu().numpy()
         for l in range(layers):
-            want = O.bottom_k(scores[l, 0].cpu().numpy().astype(np.float64), k)
-            assert sel[l, 0].cpu().numpy().tolist() == want.tolist()
-        rest = np.setdiff1d(np.arange(cfg.L_r), sel[layers - 1, 0].cpu().numpy()) + cfg.L_p
-        for w in (0, 2, 3):
-            assert torch.equal(after[w][0, rest], before[w][0, rest])
-            assert torch.equal(after[w][0, :cfg.L_p], before[w][0, :cfg.L_p])
+            for b in range(cfg.B):
+                assert sel_host[l, b].tolist() == O.bottom_k(sc_host[l, b], k).tolist()
+        for b in range(cfg.B):
+            rest = np.setdiff1d(np.arange(cfg.L_r), sel_host[layers - 1, b]) + cfg.L_p
+            for w in (0, 2, 3):
+                assert torch.equal(after[w][b, rest], before[w][b, rest])
+                assert torch.equal(after[w][b, :cfg.L_p], before[w][b, :cfg.L_p])
         den.close()
     assert all(torch.equal(a, b) for a, b in zip(runs[0], runs[1]))
 
