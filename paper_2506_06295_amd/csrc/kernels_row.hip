@@ -58,47 +58,112 @@ template <> struct IO<bf16_t, 4> {
   }
 };
 
-// sum of the S slices at one position, in slice order
-template <int V>
-__device__ __forceinline__ Vec<V> sum_slices(const float* __restrict__ c_part, int S, size_t stride,
-                                             size_t off) {
-  Vec<V> t = ld_f32<V>(c_part + off);
-  for (int s = 1; s < S; ++s) {
-    const Vec<V> u = ld_f32<V>(c_part + static_cast<size_t>(s) * stride + off);
-#pragma unroll
-    for (int e = 0; e < V; ++e) t.v[e] += u.v[e];
+// The slice count is a runtime value, but a loop over it (or a load guarded by a per-lane bounds
+// test) makes the compiler wait for every load before it issues the next one, and a row kernel
+// then spends its time in a chain of memory round trips.  So the count is dispatched to a
+// compile-time constant, every load of a row is issued unconditionally (columns past the end
+// are clamped to the last valid vector and their values ignored) and only then consumed.
+constexpr int kMaxSlicesRow = 8;
+
+#define DLLMC_SWITCH_SLICES(S, NS, ...)                   \
+  switch (S) {                                            \
+    case 1: { constexpr int NS = 1; __VA_ARGS__; } break; \
+    case 2: { constexpr int NS = 2; __VA_ARGS__; } break; \
+    case 3: { constexpr int NS = 3; __VA_ARGS__; } break; \
+    case 4: { constexpr int NS = 4; __VA_ARGS__; } break; \
+    case 5: { constexpr int NS = 5; __VA_ARGS__; } break; \
+    case 6: { constexpr int NS = 6; __VA_ARGS__; } break; \
+    case 7: { constexpr int NS = 7; __VA_ARGS__; } break; \
+    default: { constexpr int NS = 8; __VA_ARGS__; } break; \
   }
-  return t;
+
+// column of vector `it` of this thread inside the chunk starting at c0
+template <int V> __device__ __forceinline__ int chunk_col(int c0, int it) {
+  return c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+}
+// same, clamped so that a load from it stays inside a row of `width` columns
+template <int V> __device__ __forceinline__ int chunk_col_clamped(int c0, int it, int width) {
+  return min(chunk_col<V>(c0, it), width - V);
 }
 
-// Slice sums for the kRegVecs vectors of this thread inside the chunk starting at column c0
-// (vector `it` sits at column c0 + (it*kThreads + threadIdx.x)*V).  All loads are independent
-// and unrolled so that they are in flight together; the additions keep slice order.
-constexpr int kMaxSlicesRow = 8;
+// sums of NS slices at two positions, in slice order
+template <int NS>
+__device__ __forceinline__ float2 sum_slices_pair(const float* __restrict__ c_part, size_t stride,
+                                                  size_t off_a, size_t off_b) {
+  float a[NS], b[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    a[s] = c_part[static_cast<size_t>(s) * stride + off_a];
+    b[s] = c_part[static_cast<size_t>(s) * stride + off_b];
+  }
+  float2 r = make_float2(a[0], b[0]);
+#pragma unroll
+  for (int s = 1; s < NS; ++s) { r.x += a[s]; r.y += b[s]; }
+  return r;
+}
+
+// Slice sums for the kRegVecs vectors of this thread inside the chunk starting at column c0.
+// The additions keep slice order.
+template <int V, int NS>
+__device__ __forceinline__ void sum_slices_fixed(const float* __restrict__ c_part, size_t stride,
+                                                 size_t row_off, int c0, int width,
+                                                 Vec<V> (&out)[kRegVecs]) {
+  Vec<V> u[NS][kRegVecs];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it)
+      u[s][it] = ld_f32<V>(c_part + static_cast<size_t>(s) * stride + row_off +
+                           chunk_col_clamped<V>(c0, it, width));
+#pragma unroll
+  for (int it = 0; it < kRegVecs; ++it) {
+    out[it] = u[0][it];
+#pragma unroll
+    for (int s = 1; s < NS; ++s)
+#pragma unroll
+      for (int e = 0; e < V; ++e) out[it].v[e] += u[s][it].v[e];
+  }
+}
 template <int V>
 __device__ __forceinline__ void sum_slices_chunk(const float* __restrict__ c_part, int S,
                                                  size_t stride, size_t row_off, int c0, int width,
                                                  Vec<V> (&out)[kRegVecs]) {
-#pragma unroll
-  for (int it = 0; it < kRegVecs; ++it)
-#pragma unroll
-    for (int e = 0; e < V; ++e) out[it].v[e] = 0.f;
-#pragma unroll
-  for (int s = 0; s < kMaxSlicesRow; ++s) {
-    if (s < S) {
-#pragma unroll
-      for (int it = 0; it < kRegVecs; ++it) {
-        const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
-        if (c < width) {
-          const Vec<V> u = ld_f32<V>(c_part + static_cast<size_t>(s) * stride + row_off + c);
-#pragma unroll
-          for (int e = 0; e < V; ++e) out[it].v[e] += u.v[e];
-        }
-      }
-    }
-  }
+  DLLMC_SWITCH_SLICES(S, NS, sum_slices_fixed<V, NS>(c_part, stride, row_off, c0, width, out))
 }
 constexpr int kChunk(int V) { return kRegVecs * kThreads * V; }
+
+// Second pass of a row: out = x * rstd * gain (or x itself when gain is null), rounded to T,
+// to `dst` and optionally `dst2`.  The first chunk comes from registers (`keep`, `gk`); wider
+// rows re-read the float32 row this thread stored itself.
+template <typename T, int V>
+__device__ __forceinline__ void norm_store(const Vec<V> (&keep)[kRegVecs], const Vec<V>* gk,
+                                           const float* __restrict__ xr,
+                                           const T* __restrict__ gain, float rstd, int d,
+                                           T* __restrict__ dst, T* __restrict__ dst2) {
+#pragma unroll
+  for (int it = 0; it < kRegVecs; ++it) {
+    const int c = chunk_col<V>(0, it);
+    if (c < d) {
+      Vec<V> xv = keep[it];
+      if (gain != nullptr) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * gk[it].v[e];
+      }
+      IO<T, V>::st(dst + c, xv);
+      if (dst2) IO<T, V>::st(dst2 + c, xv);
+    }
+  }
+  for (int c = kChunk(V) + static_cast<int>(threadIdx.x) * V; c < d; c += kThreads * V) {
+    Vec<V> xv = ld_f32<V>(xr + c);
+    if (gain != nullptr) {
+      const Vec<V> g = IO<T, V>::ld(gain + c);
+#pragma unroll
+      for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * g.v[e];
+    }
+    IO<T, V>::st(dst + c, xv);
+    if (dst2) IO<T, V>::st(dst2 + c, xv);
+  }
+}
 
 // ---- prologue: residual stream from the embedded tokens, first attention norm ----------
 template <typename T, int V>
@@ -148,14 +213,11 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
     sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv, c0, d_kv, v);
     if (scored) {
 #pragma unroll
-      for (int it = 0; it < kRegVecs; ++it) {
-        const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
-        if (c < d_kv) o[it] = IO<T, V>::ld(vc + c);
-      }
+      for (int it = 0; it < kRegVecs; ++it) o[it] = IO<T, V>::ld(vc + chunk_col_clamped<V>(c0, it, d_kv));
     }
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
-      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      const int c = chunk_col<V>(c0, it);
       if (c < d_kv) {
 #pragma unroll
         for (int e = 0; e < V; ++e) v[it].v[e] = roundf_to<T>(v[it].v[e]);
@@ -204,11 +266,11 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
                     : k_cache + static_cast<size_t>(row) * d_kv + (c0 - d_q);
   for (int t = threadIdx.x; t < half; t += 64) {
     const size_t off = static_cast<size_t>(i) * width + c0 + t;
-    const float a = sum_slices<1>(c_part, S, slice_stride, off).v[0];
-    const float b = sum_slices<1>(c_part, S, slice_stride, off + half).v[0];
+    float2 ab;
+    DLLMC_SWITCH_SLICES(S, NS, ab = sum_slices_pair<NS>(c_part, slice_stride, off, off + half))
     const float2 cs = tab[t];
-    stf(dst + t, a * cs.x - b * cs.y);
-    stf(dst + t + half, b * cs.x + a * cs.y);
+    stf(dst + t, ab.x * cs.x - ab.y * cs.y);
+    stf(dst + t + half, ab.y * cs.x + ab.x * cs.y);
   }
 }
 
@@ -234,15 +296,13 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
     if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, a);
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
-      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
-      if (c < d) {
-        if (ci < 0) a[it] = IO<T, V>::ld(ac + c);
-        xv[it] = ld_f32<V>(xr + c);
-      }
+      const int c = chunk_col_clamped<V>(c0, it, d);
+      if (ci < 0) a[it] = IO<T, V>::ld(ac + c);
+      xv[it] = ld_f32<V>(xr + c);
     }
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
-      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      const int c = chunk_col<V>(c0, it);
       if (c < d) {
         if (ci >= 0) {
 #pragma unroll
@@ -259,19 +319,15 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
       }
     }
   }
-  int it = 0;
   if (ci < 0) return;  // uniform over the workgroup
+  // gain vectors of the first chunk: issued before the reduction so they arrive under it
+  Vec<V> gk[kRegVecs];
+#pragma unroll
+  for (int it = 0; it < kRegVecs; ++it) gk[it] = IO<T, V>::ld(gain + chunk_col_clamped<V>(0, it, d));
   ss = block_sum<kNW>(ss, red);
   const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
   T* gr = g_out + static_cast<size_t>(ci) * d;
-  it = 0;
-  for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
-    Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
-    const Vec<V> g = IO<T, V>::ld(gain + c);
-#pragma unroll
-    for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * g.v[e];
-    IO<T, V>::st(gr + c, xv);
-  }
+  norm_store<T, V>(keep, gk, xr, gain, rstd, d, gr, nullptr);
 }
 
 // ---- SwiGLU product (only when the fused gate/up kernel does not apply) -------------------
@@ -283,9 +339,9 @@ __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c
   const int j = blockIdx.x * kThreads + threadIdx.x;
   if (j >= m) return;
   const size_t off = static_cast<size_t>(i) * 2 * m + j;
-  const float g = sum_slices<1>(c_part, S, slice_stride, off).v[0];
-  const float up = sum_slices<1>(c_part, S, slice_stride, off + m).v[0];
-  stf(u + static_cast<size_t>(i) * m + j, g / (1.0f + expf(-g)) * up);
+  float2 gu;
+  DLLMC_SWITCH_SLICES(S, NS, gu = sum_slices_pair<NS>(c_part, slice_stride, off, off + m))
+  stf(u + static_cast<size_t>(i) * m + j, gu.x / (1.0f + expf(-gu.x)) * gu.y);
 }
 
 // ---- down projection epilogue + residual + next layer's attention norm / step output ------
@@ -307,15 +363,13 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
     if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, f);
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
-      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
-      if (c < d) {
-        if (ci < 0) f[it] = IO<T, V>::ld(fc + c);
-        xv[it] = ld_f32<V>(xr + c);
-      }
+      const int c = chunk_col_clamped<V>(c0, it, d);
+      if (ci < 0) f[it] = IO<T, V>::ld(fc + c);
+      xv[it] = ld_f32<V>(xr + c);
     }
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
-      const int c = c0 + (it * kThreads + static_cast<int>(threadIdx.x)) * V;
+      const int c = chunk_col<V>(c0, it);
       if (c < d) {
         if (ci >= 0) {
 #pragma unroll
@@ -332,31 +386,20 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
       }
     }
   }
-  int it = 0;
   if (next_gain != nullptr) {
+    Vec<V> gk[kRegVecs];
+#pragma unroll
+    for (int it = 0; it < kRegVecs; ++it) gk[it] = IO<T, V>::ld(next_gain + chunk_col_clamped<V>(0, it, d));
     ss = block_sum<kNW>(ss, red);
     const float rstd = 1.0f / sqrtf(ss / static_cast<float>(d) + eps);
-    T* hr = h + static_cast<size_t>(row) * d;
-    it = 0;
-    for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
-      Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
-      const Vec<V> g = IO<T, V>::ld(next_gain + c);
-#pragma unroll
-      for (int e = 0; e < V; ++e) xv.v[e] = xv.v[e] * rstd * g.v[e];
-      IO<T, V>::st(hr + c, xv);
-    }
+    norm_store<T, V>(keep, gk, xr, next_gain, rstd, d, h + static_cast<size_t>(row) * d, nullptr);
   } else {
     T* o = hidden_out + static_cast<size_t>(row) * d;
     const int pos = row % n;
     T* po = (prompt_out != nullptr && pos < L_p)
                 ? prompt_out + (static_cast<size_t>(row / n) * L_p + pos) * d
                 : nullptr;
-    it = 0;
-    for (int c = threadIdx.x * V; c < d; c += kThreads * V, ++it) {
-      const Vec<V> xv = it < kRegVecs ? keep[it] : ld_f32<V>(xr + c);
-      IO<T, V>::st(o + c, xv);
-      if (po) IO<T, V>::st(po + c, xv);
-    }
+    norm_store<T, V>(keep, nullptr, xr, nullptr, 1.0f, d, o, po);
   }
 }
 
