@@ -274,18 +274,28 @@ __global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ par
                                                    bf16_t* __restrict__ out) {
   const size_t qh = static_cast<size_t>(blockIdx.x);  // (b*Mq + iq)*H_q + a
   const float* w = part + qh * KS * (kDH + 2);
-  float M = -INFINITY;
-  for (int r = 0; r < KS; ++r) M = fmaxf(M, w[r * (kDH + 2) + kDH]);
-  float L = 0.f, o0 = 0.f, o1 = 0.f;
+  // All kMaxKeySplit slots are loaded before the first use (slots past KS re-read the last
+  // valid one and get weight zero): a loop over the runtime count would wait for each load.
   const int dim = threadIdx.x * 2;
-  for (int r = 0; r < KS; ++r) {
-    const float* wr = w + r * (kDH + 2);
-    const float mr = wr[kDH];
-    const float f = mr == -INFINITY ? 0.f : exp2f(mr - M);
-    L += wr[kDH + 1] * f;
-    const float2 o = *reinterpret_cast<const float2*>(wr + dim);
-    o0 += o.x * f;
-    o1 += o.y * f;
+  float mr[kMaxKeySplit], lr[kMaxKeySplit];
+  float2 o[kMaxKeySplit];
+#pragma unroll
+  for (int r = 0; r < kMaxKeySplit; ++r) {
+    const float* wr = w + min(r, KS - 1) * (kDH + 2);
+    mr[r] = wr[kDH];
+    lr[r] = wr[kDH + 1];
+    o[r] = *reinterpret_cast<const float2*>(wr + dim);
+  }
+  float M = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < kMaxKeySplit; ++r) M = fmaxf(M, mr[r]);
+  float L = 0.f, o0 = 0.f, o1 = 0.f;
+#pragma unroll
+  for (int r = 0; r < kMaxKeySplit; ++r) {
+    const float f = (r >= KS || mr[r] == -INFINITY) ? 0.f : exp2f(mr[r] - M);
+    L += lr[r] * f;
+    o0 += o[r].x * f;
+    o1 += o[r].y * f;
   }
   const uint32_t t = static_cast<uint32_t>(f32_to_bf16(o0 / L)) |
                      (static_cast<uint32_t>(f32_to_bf16(o1 / L)) << 16);

@@ -1,6 +1,6 @@
 // Gathered linear maps  C[i, :] = A[rows[i], :] * W^T  (W row-major [N, K], K contiguous).
 //
-// Two kernels:
+// Kernels:
 //  * k_gemm_simple  -- plain LDS-tiled FMA kernel for any storage type and shape (used for
 //                      float32 models and as the fallback for shapes the MFMA kernel
 //                      does not take).
@@ -13,6 +13,9 @@
 //                      index is split over workgroups to put >= 2 workgroups on every CU.
 //                      Partial sums go to float32 slices that the row kernels add up in a
 //                      fixed order (no float atomics: results are bit-reproducible).
+//  * k_gemm_fat / k_gemm_mid -- bf16 MFMA kernels with 256 x 256 / 128 x 128 tiles whose
+//                      operands both go through LDS by direct global->LDS loads, for
+//                      launches with hundreds of activation rows.
 #include "common.hpp"
 
 namespace dllmc {
@@ -254,135 +257,137 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 }
 
 // ------------------------------------------------------------------------------------
-// k_gemm_tile: bf16 MFMA kernel for many activation rows (refresh steps, V projection of all
-// response rows, batched sequences), where the work is bound by the matrix cores rather than
-// by the weight stream.  Workgroup = 4 wavefronts (2 x 2), tile = 128 rows x 128 columns,
-// each wavefront 64 x 64 as 4 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands
-// go through LDS in 64-wide steps of the contraction index; the next step's tiles are
-// fetched into registers while the current one is multiplied (one barrier per step).
-// blockIdx.z selects a slice of the contraction index; float32 partial sums go to slice z of C.
-constexpr int kTileM = 128, kTileN = 128, kTileK = 64, kTileLS = kTileK + 8;
-
-__global__ __launch_bounds__(256) void k_gemm_tile(const bf16_t* __restrict__ A, int lda,
-                                                   const int* __restrict__ rows, int M,
-                                                   const bf16_t* __restrict__ W0,
-                                                   const bf16_t* __restrict__ W1, int N0, int N,
-                                                   int K, int k_per_slice, float* __restrict__ C) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][kTileM * kTileLS];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][kTileN * kTileLS];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  const int ln = lane % 16, lg = lane / 16;
-  const int wm = wave / 2, wn = wave % 2;  // wavefront position inside the tile
-  int col_tile, row_tile;
-  xcd_tile_map(col_tile, row_tile);
-  const int m0 = row_tile * kTileM, n0 = col_tile * kTileN;
-  const int kbeg = blockIdx.z * k_per_slice;
-  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kTileK
-  const int nkt = klen / kTileK;
-
-  // staging: 128 rows x 8 chunks of 16 bytes per operand and step, four chunks per thread
-  const bf16_t* asrc[4];
-  const bf16_t* bsrc[4];
-  int dst[4];
-  bool aval[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int e = threadIdx.x + j * 256;
-    const int r = e / 8, c = e % 8;
-    const int m = m0 + r;
-    aval[j] = m < M;
-    const int row = aval[j] ? (rows ? rows[m] : m) : 0;
-    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + c * 8;
-    const int nn = n0 + r;  // < N: N % 128 == 0
-    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
-              kbeg + c * 8;
-    dst[j] = r * kTileLS + c * 8;
-  }
-  f32x4 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  uint4 ra[4], rb[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    ra[j] = aval[j] ? *reinterpret_cast<const uint4*>(asrc[j]) : make_uint4(0u, 0u, 0u, 0u);
-    rb[j] = *reinterpret_cast<const uint4*>(bsrc[j]);
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    *reinterpret_cast<uint4*>(&As[0][dst[j]]) = ra[j];
-    *reinterpret_cast<uint4*>(&Bs[0][dst[j]]) = rb[j];
-  }
-  __syncthreads();
-
-  for (int kt = 0; kt < nkt; ++kt) {
-    const bool more = kt + 1 < nkt;
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        ra[j] = aval[j] ? *reinterpret_cast<const uint4*>(asrc[j] + (kt + 1) * kTileK)
-                        : make_uint4(0u, 0u, 0u, 0u);
-        rb[j] = *reinterpret_cast<const uint4*>(bsrc[j] + (kt + 1) * kTileK);
-      }
-    }
-    const bf16_t* ap = &As[kt & 1][(wm * 64 + ln) * kTileLS + lg * 8];
-    const bf16_t* bp = &Bs[kt & 1][(wn * 64 + ln) * kTileLS + lg * 8];
-#pragma unroll
-    for (int ks = 0; ks < kTileK; ks += 32) {
-      bf16x8 af[4], bf[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(ap + i * 16 * kTileLS + ks);
-        bf[i] = *reinterpret_cast<const bf16x8*>(bp + i * 16 * kTileLS + ks);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        *reinterpret_cast<uint4*>(&As[(kt + 1) & 1][dst[j]]) = ra[j];
-        *reinterpret_cast<uint4*>(&Bs[(kt + 1) & 1][dst[j]]) = rb[j];
-      }
-    }
-    __syncthreads();
-  }
-
-  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int m = m0 + wm * 64 + i * 16 + lg * 4 + e;
-      if (m < M) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          Cs[static_cast<size_t>(m) * N + n0 + wn * 64 + j * 16 + ln] = acc[i][j][e];
-      }
-    }
-}
-
-// ------------------------------------------------------------------------------------
-// k_gemm_fat: bf16 MFMA kernel for many activation rows with a 256 x 256 tile, so that every
-// byte pulled from L2 feeds 128 flops.  Workgroup = 8 wavefronts (2 x 4), each 128 rows x 64
-// columns = 8 x 4 accumulators of v_mfma_f32_16x16x32_bf16.  Both operands reach LDS with
+// LDS-direct MFMA kernels for many activation rows (refresh steps, the V projection of all
+// response rows, batched sequences), where the work is bound by the matrix cores and by L2
+// rather than by the weight stream.  Workgroup = WM x WN wavefronts, each (16*MI) rows x
+// (16*NJ) columns of v_mfma_f32_16x16x32_bf16 accumulators.  Both operands reach LDS with
 // global_load_lds_dwordx4 (no VGPR staging): a wavefront instruction copies 8 rows x 128
 // contiguous bytes (64 values of the contraction index) into 1 KB of LDS in lane order, i.e.
 // LDS holds [row][8 slots of 16 bytes]; the slot of chunk c of row r is c ^ (r % 8) so that
 // the 16-byte fragment reads of 8 consecutive rows hit 8 different bank groups.  Two LDS
-// stages of 64 KB: the loads of step t+1 are in flight while step t is multiplied.
+// stages: the loads of step t+1 are in flight while step t is multiplied.
 // Rows beyond M read a valid row again and are dropped at the store.
+//   fat: 2 x 4 wavefronts of 128 x 64 -> 256 x 256 tile (every byte pulled from L2 feeds 128
+//        flops), 128 KB of LDS, one workgroup per CU: M >= fat_min_m.
+//   mid: 2 x 2 wavefronts of  64 x 64 -> 128 x 128 tile, 64 KB of LDS, two workgroups per CU:
+//        enough tiles to fill the chip when M is a few hundred rows.
 constexpr int kFatM = 256, kFatN = 256, kFatK = 64;
+constexpr int kMidM = 128, kMidN = 128;
 
-__device__ __forceinline__ void wait_vmcnt(int n) {
-  // s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
-  if (n == 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-  else __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8)
+// s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int WM, int WN, int MI, int NJ>
+__device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int lda,
+                                              const int* __restrict__ rows, int M,
+                                              const bf16_t* __restrict__ W0,
+                                              const bf16_t* __restrict__ W1, int N0, int N, int K,
+                                              int k_per_slice, float* __restrict__ C) {
+  constexpr int NWV = WM * WN;
+  constexpr int BM = WM * MI * 16, BN = WN * NJ * 16;
+  constexpr int LA = BM / 8 / NWV, LB = BN / 8 / NWV;  // load instructions per wavefront and step
+  static_assert(BM % (8 * NWV) == 0 && BN % (8 * NWV) == 0, "loader must divide evenly");
+  // [stage][activation rows, then weight rows][8 slots], 16 bytes each
+  __shared__ __attribute__((aligned(1024))) uint4 lds[2][(BM + BN) * 8];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int wm = wave / WN, wn = wave % WN;
+  int col_tile, row_tile;
+  xcd_tile_map(col_tile, row_tile);
+  const int m0 = row_tile * BM, n0 = col_tile * BN;
+  const int kbeg = blockIdx.z * k_per_slice;
+  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kFatK
+  const int nkt = klen / kFatK;
+
+  // loader: instruction q of an operand covers rows [8q, 8q+8); wavefront w issues
+  // q = L*w .. L*w+L-1.  Lane l: row 8q + l/8, LDS slot l%8, global chunk (l%8) ^ (row%8).
+  const bf16_t* asrc[LA];
+  const bf16_t* bsrc[LB];
+#pragma unroll
+  for (int j = 0; j < LA; ++j) {
+    const int r = 8 * (LA * wave + j) + lane / 8;
+    const int chunk = (lane % 8) ^ (r % 8);
+    int m = m0 + r;
+    if (m >= M) m = M - 1;
+    const int row = rows ? rows[m] : m;
+    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + chunk * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < LB; ++j) {
+    const int r = 8 * (LB * wave + j) + lane / 8;
+    const int chunk = (lane % 8) ^ (r % 8);
+    const int nn = n0 + r;  // < N: N % BN == 0
+    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
+              kbeg + chunk * 8;
+  }
+#define DLLMC_LDS_ISSUE(stage, kt)                                                              \
+  {                                                                                             \
+    _Pragma("unroll") for (int j = 0; j < LA; ++j) __builtin_amdgcn_global_load_lds(            \
+        asrc[j] + (kt) * kFatK, &lds[stage][(LA * wave + j) * 64], 16, 0, 0);                   \
+    _Pragma("unroll") for (int j = 0; j < LB; ++j) __builtin_amdgcn_global_load_lds(            \
+        bsrc[j] + (kt) * kFatK, &lds[stage][BM * 8 + (LB * wave + j) * 64], 16, 0, 0);          \
+  }
+
+  f32x4 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  DLLMC_LDS_ISSUE(0, 0)
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < nkt;
+    if (more) {
+      DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
+      wait_vmcnt<LA + LB>();  // this wavefront's loads of step kt have landed
+    } else {
+      wait_vmcnt<0>();
+    }
+    // bare barrier (no memory fence: a fence would wait for the loads of step kt+1 as well)
+    __builtin_amdgcn_s_barrier();  // ... and everybody else's
+    const uint4* la = &lds[cur][0];
+    const uint4* lb = &lds[cur][BM * 8];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int c = kk * 4 + lg;  // 16-byte chunk of the 64-wide step this lane group multiplies
+      bf16x8 af[MI], bf[NJ];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int r = wm * (MI * 16) + i * 16 + ln;
+        af[i] = __builtin_bit_cast(bf16x8, la[r * 8 + (c ^ (r % 8))]);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int r = wn * (NJ * 16) + j * 16 + ln;
+        bf[j] = __builtin_bit_cast(bf16x8, lb[r * 8 + (c ^ (r % 8))]);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    // all LDS reads of this stage are complete (their results fed the MFMAs above) before the
+    // loads issued in the next iteration overwrite it
+    __builtin_amdgcn_s_barrier();
+  }
+#undef DLLMC_LDS_ISSUE
+
+  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int m = m0 + wm * (MI * 16) + i * 16 + lg * 4 + e;
+      if (m < M) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          Cs[static_cast<size_t>(m) * N + n0 + wn * (NJ * 16) + j * 16 + ln] = acc[i][j][e];
+      }
+    }
 }
 
 __global__ __launch_bounds__(512) void k_gemm_fat(const bf16_t* __restrict__ A, int lda,
@@ -390,94 +395,15 @@ __global__ __launch_bounds__(512) void k_gemm_fat(const bf16_t* __restrict__ A, 
                                                   const bf16_t* __restrict__ W0,
                                                   const bf16_t* __restrict__ W1, int N0, int N,
                                                   int K, int k_per_slice, float* __restrict__ C) {
-  // [stage][operand (0 = activations, 1 = weights)][row * 8 + slot], 16 bytes each
-  __shared__ __attribute__((aligned(1024))) uint4 lds[2][2][kFatM * 8];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  const int ln = lane % 16, lg = lane / 16;
-  const int wm = wave / 4, wn = wave % 4;
-  int col_tile, row_tile;
-  xcd_tile_map(col_tile, row_tile);
-  const int m0 = row_tile * kFatM, n0 = col_tile * kFatN;
-  const int kbeg = blockIdx.z * k_per_slice;
-  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kFatK
-  const int nkt = klen / kFatK;
+  gemm_lds_body<2, 4, 8, 4>(A, lda, rows, M, W0, W1, N0, N, K, k_per_slice, C);
+}
 
-  // loader: instruction q (0..31) of an operand covers rows [8q, 8q+8); wavefront w issues
-  // q = 4w .. 4w+3.  Lane l: row 8q + l/8, LDS slot l%8, global chunk (l%8) ^ (row%8).
-  const bf16_t* asrc[4];
-  const bf16_t* bsrc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int r = 8 * (4 * wave + j) + lane / 8;
-    const int chunk = (lane % 8) ^ (r % 8);
-    int m = m0 + r;
-    if (m >= M) m = M - 1;
-    const int row = rows ? rows[m] : m;
-    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + chunk * 8;
-    const int nn = n0 + r;  // < N: N % 256 == 0
-    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
-              kbeg + chunk * 8;
-  }
-  auto issue = [&](int stage, int kt) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = 4 * wave + j;
-      __builtin_amdgcn_global_load_lds(asrc[j] + kt * kFatK, &lds[stage][0][q * 64], 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(bsrc[j] + kt * kFatK, &lds[stage][1][q * 64], 16, 0, 0);
-    }
-  };
-
-  f32x4 acc[8][4];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  issue(0, 0);
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < nkt;
-    if (more) issue(cur ^ 1, kt + 1);
-    wait_vmcnt(more ? 8 : 0);  // this wavefront's loads of step kt have landed
-    // bare barrier (no memory fence: a fence would wait for the loads of step kt+1 as well)
-    __builtin_amdgcn_s_barrier();  // ... and everybody else's
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const int c = kk * 4 + lg;  // 16-byte chunk of the 64-wide step this lane group multiplies
-      bf16x8 af[8], bf[4];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = wm * 128 + i * 16 + ln;
-        af[i] = __builtin_bit_cast(bf16x8, lds[cur][0][r * 8 + (c ^ (r % 8))]);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int r = wn * 64 + j * 16 + ln;
-        bf[j] = __builtin_bit_cast(bf16x8, lds[cur][1][r * 8 + (c ^ (r % 8))]);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-    }
-    // all LDS reads of this stage are complete (their results fed the MFMAs above) before the
-    // loads issued in the next iteration overwrite it
-    __builtin_amdgcn_s_barrier();
-  }
-
-  float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int m = m0 + wm * 128 + i * 16 + lg * 4 + e;
-      if (m < M) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          Cs[static_cast<size_t>(m) * N + n0 + wn * 64 + j * 16 + ln] = acc[i][j][e];
-      }
-    }
+__global__ __launch_bounds__(256) void k_gemm_mid(const bf16_t* __restrict__ A, int lda,
+                                                  const int* __restrict__ rows, int M,
+                                                  const bf16_t* __restrict__ W0,
+                                                  const bf16_t* __restrict__ W1, int N0, int N,
+                                                  int K, int k_per_slice, float* __restrict__ C) {
+  gemm_lds_body<2, 2, 4, 4>(A, lda, rows, M, W0, W1, N0, N, K, k_per_slice, C);
 }
 
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
@@ -503,8 +429,8 @@ struct GemmTuning {
   int nw_dual = 4;     // same for the fused gate/up kernel
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
-  int fat_min_m = 384;      // activation rows from which the 256 x 256 LDS-direct kernel is used
-  int tile_min_m = 1 << 30; // activation rows from which the 128 x 128 tile kernel is used
+  int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
+  int tile_min_m = 192;     // activation rows from which the 128 x 128 LDS-direct kernel is used
                             // (off by default: the streaming kernel is faster at the sizes measured)
 } g_tune;
 
@@ -583,15 +509,16 @@ GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int 
     p.S = (K + p.kps - 1) / p.kps;
     return p;
   }
-  if (M >= g_tune.tile_min_m && N % kTileN == 0 && N0 % kTileN == 0 && K % kTileK == 0) {
+  if (M >= g_tune.tile_min_m && N % kMidN == 0 && N0 % kMidN == 0 && K % kFatK == 0) {
     p.kind = 4;
-    p.mt = (M + kTileM - 1) / kTileM;
-    p.nt = N / kTileN;
+    p.mt = (M + kMidM - 1) / kMidM;
+    p.nt = N / kMidN;
+    // two workgroups per CU: aim at 512 tiles in flight, at least 8 steps of 64 per slice
     int S = g_tune.force_s > 0 ? g_tune.force_s
-                               : (2 * g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
+                               : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
     S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
-    p.kps = ((K + S - 1) / S + kTileK - 1) / kTileK * kTileK;
-    if (p.kps < 4 * kTileK) p.kps = 4 * kTileK;
+    p.kps = ((K + S - 1) / S + kFatK - 1) / kFatK * kFatK;
+    if (p.kps < 8 * kFatK) p.kps = 8 * kFatK;
     if (p.kps > K) p.kps = K;
     p.S = (K + p.kps - 1) / p.kps;
     return p;
@@ -639,7 +566,7 @@ int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const
                          c_part);
       break;
     case 4:
-      hipLaunchKernelGGL(k_gemm_tile, grid, dim3(256), 0, st, a, lda, rows, M, w0, w1, N0, N, K,
+      hipLaunchKernelGGL(k_gemm_mid, grid, dim3(256), 0, st, a, lda, rows, M, w0, w1, N0, N, K,
                          p.kps, c_part);
       break;
     default: {

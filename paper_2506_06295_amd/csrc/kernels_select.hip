@@ -15,6 +15,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kNW = kThreads / kWave;
+constexpr int kKeysInLds = 8192;  // response lengths up to this keep their keys in LDS
 
 __device__ __forceinline__ uint32_t order_key(float s) {
   s += 0.0f;  // -0.0 -> +0.0 so that the two zeros tie
@@ -54,8 +55,15 @@ __global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ s
   __shared__ uint32_t hist[256];
   __shared__ uint32_t scan_scratch[kNW + 1];
   __shared__ uint32_t sh_prefix, sh_need;
+  __shared__ uint32_t keys[kKeysInLds];
   const int b = blockIdx.x;
   const float* s = scores + static_cast<size_t>(b) * L;
+  // The five passes below read every key; one trip to global memory instead of five when the
+  // sequence fits the LDS buffer (the visibility of `keys` rides on the first barrier below).
+  const bool in_lds = L <= kKeysInLds;
+  if (in_lds)
+    for (int j = threadIdx.x; j < L; j += kThreads) keys[j] = order_key(s[j]);
+  if (k <= 0) __syncthreads();
 
   uint32_t kth = 0, need = 0;
   if (k > 0) {
@@ -67,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ s
       hist[threadIdx.x] = 0;
       __syncthreads();
       for (int j = threadIdx.x; j < L; j += kThreads) {
-        const uint32_t key = order_key(s[j]);
+        const uint32_t key = in_lds ? keys[j] : order_key(s[j]);
         if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
       }
       __syncthreads();
@@ -91,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ s
   for (int j0 = 0; j0 < L; j0 += kThreads) {
     const int j = j0 + threadIdx.x;
     const bool valid = j < L;
-    const uint32_t key = valid ? order_key(s[j]) : 0xFFFFFFFFu;
+    const uint32_t key = valid ? (in_lds ? keys[j] : order_key(s[j])) : 0xFFFFFFFFu;
     const bool less = valid && k > 0 && key < kth;
     const bool eq = valid && k > 0 && key == kth;
     uint32_t tot_eq, tot_take;

@@ -108,7 +108,7 @@ def test_linear_tile_kernel(M, N, K):
     try:
         run_linear_case("bf16", M, N, K, True)
     finally:
-        binding.set_gemm_tuning(tile_min_m=1 << 30)
+        binding.set_gemm_tuning(tile_min_m=192)
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 1024, 4096), (300, 512, 896), (768, 2304, 1024), (100, 256, 512)])
@@ -117,7 +117,7 @@ def test_linear_fat_kernel(M, N, K):
     try:
         run_linear_case("bf16", M, N, K, True)
     finally:
-        binding.set_gemm_tuning(fat_min_m=384)
+        binding.set_gemm_tuning(fat_min_m=1024)
 
 
 def run_linear_case(dtype, M, N, K, gather):
