@@ -140,7 +140,9 @@ int dllmc_last_hip_error(void);
 
 /* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
  * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
- * of the fused gate/up kernel, force_s number of contraction slices (0 = automatic), target_wg
+ * of the fused gate/up kernel (nw_dual + 100: the wavefronts of a workgroup form two groups
+ * that each walk one half of the contraction range), force_s number of contraction slices
+ * (0 = automatic), target_wg
  * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
  * from which the 128 x 128 tile kernel / the 256 x 256 LDS-direct kernel replaces the
  * weight-streaming kernel.  Results are

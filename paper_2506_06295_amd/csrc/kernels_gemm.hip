@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 }
 
 // ------------------------------------------------------------------------------------
-// k_gemm_stream<NW, KC, DUAL>
+// k_gemm_stream<NW, KC, DUAL, KH>
 // Workgroup = NW wavefronts; tile = 64 activation rows x (16*NW) output columns; wavefront w
 // owns 16 columns and all 64 rows (four 16x16 accumulators of v_mfma_f32_16x16x32_bf16 per
 // weight matrix).  The workgroup's slice of the contraction index is walked in phases of KC:
@@ -121,47 +121,56 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 //   DUAL = 1: every lane streams row n of W0 (gate) and row n of W1 (up) and the epilogue
 //             stores bf16(silu(gate) * up) to U[M, N] (SwiGLU, complexity appendix of the
 //             paper); needs a single slice.
-template <int NW, int KC, int DUAL>
+//   KH = 2:   the wavefronts form two groups that walk the two halves of the workgroup's
+//             contraction range side by side (tile = 16*NW/2 columns); the second group hands
+//             its accumulators over through LDS at the end and the first adds them (its own
+//             sum first).  Doubles the wavefronts, and with them the loads in flight, of a
+//             launch that cannot split the contraction over workgroups (DUAL).
+template <int NW, int KC, int DUAL, int KH>
 __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, int N0, int N, int K,
     int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
-  constexpr int LS = KC + 8;                 // LDS row stride: rows start 4 banks apart
-  constexpr int CPR = KC / 8;                // 16-byte chunks per activation row and phase
-  constexpr int NCH = 64 * CPR / (NW * 64);  // chunks staged per thread and phase
+  constexpr int LS = KC + 8;                      // LDS row stride: rows start 4 banks apart
+  constexpr int CPR = KC / 8;                     // 16-byte chunks per activation row and phase
+  constexpr int NCH = KH * 64 * CPR / (NW * 64);  // chunks staged per thread and phase
   constexpr int NB = DUAL ? 2 : 1;
-  static_assert((64 * CPR) % (NW * 64) == 0 && NCH >= 1, "staging must divide evenly");
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][64 * LS];
+  constexpr int NWC = NW / KH;                    // wavefronts side by side over the columns
+  static_assert((KH * 64 * CPR) % (NW * 64) == 0 && NCH >= 1, "staging must divide evenly");
+  static_assert(NW % KH == 0, "wavefront groups must be equal");
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][KH][64 * LS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
+  const int wcol = wave % NWC, kh = wave / NWC;
   int col_tile, row_tile;
   xcd_tile_map(col_tile, row_tile);
   const int m0 = row_tile * 64;
   const int kbeg = blockIdx.z * k_per_slice;
-  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KC
-  const int nph = klen / KC;
-  const int ncol = col_tile * (16 * NW) + wave * 16 + ln;  // < N: N % (16*NW) == 0
+  const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KH * KC
+  const int hlen = klen / KH;                          // contraction range of one group
+  const int nph = hlen / KC;
+  const int ncol = col_tile * (16 * NWC) + wcol * 16 + ln;  // < N: N % (16*NWC) == 0
   const bf16_t* wp[NB];
   if (DUAL) {
-    wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + lg * 8;
-    wp[NB - 1] = W1 + static_cast<size_t>(ncol) * K + kbeg + lg * 8;
+    wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + kh * hlen + lg * 8;
+    wp[NB - 1] = W1 + static_cast<size_t>(ncol) * K + kbeg + kh * hlen + lg * 8;
   } else {
     wp[0] = (ncol < N0 ? W0 + static_cast<size_t>(ncol) * K
-                       : W1 + static_cast<size_t>(ncol - N0) * K) + kbeg + lg * 8;
+                       : W1 + static_cast<size_t>(ncol - N0) * K) + kbeg + kh * hlen + lg * 8;
   }
-  // the activation chunks this thread stages: same (row, chunk) in every phase
+  // the activation chunks this thread stages: same (group, row, chunk) in every phase
   const bf16_t* asrc[NCH];
   int adst[NCH];
   bool aval[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int e = threadIdx.x + j * NW * 64;
-    const int r = e / CPR, c = e % CPR;
+    const int h = e / (64 * CPR), r = (e / CPR) % 64, c = e % CPR;
     const int m = m0 + r;
     aval[j] = m < M;
     const int row = aval[j] ? (rows ? rows[m] : m) : 0;
-    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + c * 8;
-    adst[j] = r * LS + c * 8;
+    asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + h * hlen + c * 8;
+    adst[j] = h * 64 * LS + r * LS + c * 8;
   }
   f32x4 acc[NB][4];
 #pragma unroll
@@ -173,7 +182,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   for (int j = 0; j < NCH; ++j) {
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j]);
-    *reinterpret_cast<uint4*>(&As[0][adst[j]]) = v;
+    *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = v;
   }
   // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
   constexpr int NS = KC / 128;
@@ -197,7 +206,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
         if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + (ph + 1) * KC);
       }
     }
-    const bf16_t* ap = &As[ph & 1][ln * LS + lg * 8];
+    const bf16_t* ap = &As[ph & 1][kh][ln * LS + lg * 8];
 #pragma unroll
     for (int t = 0; t < NS; ++t) {
       uint4 bc[NB][4];
@@ -228,9 +237,33 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     if (more) {
 #pragma unroll
       for (int j = 0; j < NCH; ++j)
-        *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][adst[j]]) = av[j];
+        *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][0][adst[j]]) = av[j];
     }
     __syncthreads();
+  }
+
+  if (KH > 1) {
+    // hand-over of the second group's sums: [column wavefront][matrix][accumulator element][lane]
+    // (every LDS read of the activation tiles is behind the barrier that ended the last phase)
+    float* red = reinterpret_cast<float*>(&As[0][0][0]);
+    if (kh > 0) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
+    }
+    __syncthreads();
+    if (kh > 0) return;
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[b][mb][i] += red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane];
   }
 
   if (DUAL) {
@@ -426,7 +459,7 @@ void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, 
 namespace {
 struct GemmTuning {
   int nw = 8;          // wavefronts per workgroup (4 or 8) of the single-matrix kernel
-  int nw_dual = 4;     // same for the fused gate/up kernel
+  int nw_dual = 108;   // fused gate/up kernel: 8 wavefronts, two groups over the contraction range
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
   int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
@@ -436,11 +469,11 @@ struct GemmTuning {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int NW, int KC, int DUAL>
+template <int NW, int KC, int DUAL, int KH = 1>
 void launch_stream(dim3 grid, hipStream_t st, const bf16_t* A, int lda, const int* rows, int M,
                    const bf16_t* W0, const bf16_t* W1, int N0, int N, int K, int kps, float* C,
                    bf16_t* U) {
-  hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
+  hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL, KH>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
                      W1, N0, N, K, kps, C, U);
 }
 
@@ -455,14 +488,14 @@ void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
   if (nw == 4 || nw == 8) g_tune.nw = nw;
-  if (nw_dual == 4 || nw_dual == 8) g_tune.nw_dual = nw_dual;
+  if (nw_dual == 4 || nw_dual == 8 || nw_dual == 104 || nw_dual == 108) g_tune.nw_dual = nw_dual;
   if (force_s >= 0) g_tune.force_s = force_s;
   if (target_wg > 0) g_tune.target_wg = target_wg;
 }
 
 // Which kernel, how many slices of the contraction index and how long a slice: pure host logic.
 struct GemmPlan {
-  int kind;  // 0 nothing fits, 1 plain, 2 streaming, 3 256x256 LDS-direct, 4 128x128 tile
+  int kind;  // 0 nothing fits, 1 plain, 2 streaming, 3 256x256 LDS-direct, 4 128x128 LDS-direct
   int S, kps, KC, nt, mt;
 };
 
@@ -587,21 +620,27 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
                         const void* w_gate, const void* w_up, int m, int K, void* u,
                         hipStream_t st) {
   if (M <= 0 || m <= 0) return true;
-  const int NW = g_tune.nw_dual;
-  if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % (16 * NW) == 0) || M > 128)
-    return false;
+  const int NW = g_tune.nw_dual % 100;  // wavefronts per workgroup
   const int KC = (K % 256 == 0) ? 256 : 128;
-  const dim3 grid(m / (16 * NW), (M + 63) / 64, 1);
+  // two wavefront groups over the two halves of K when the halves are whole phases
+  const int KH = (g_tune.nw_dual >= 100 && K % (2 * KC) == 0) ? 2 : 1;
+  const int BN = 16 * NW / KH;
+  if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % BN == 0) || M > 128) return false;
+  const dim3 grid(m / BN, (M + 63) / 64, 1);
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
   const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
   bf16_t* uo = static_cast<bf16_t*>(u);
-#define DLLMC_GD(NWv, KCv) \
-  launch_stream<NWv, KCv, 1>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
-  if (NW == 8) {
-    if (KC == 256) DLLMC_GD(8, 256); else DLLMC_GD(8, 128);
+#define DLLMC_GD(NWv, KCv, KHv) \
+  launch_stream<NWv, KCv, 1, KHv>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
+  if (NW == 8 && KH == 2) {
+    if (KC == 256) DLLMC_GD(8, 256, 2); else DLLMC_GD(8, 128, 2);
+  } else if (NW == 8) {
+    if (KC == 256) DLLMC_GD(8, 256, 1); else DLLMC_GD(8, 128, 1);
+  } else if (KH == 2) {
+    if (KC == 256) DLLMC_GD(4, 256, 2); else DLLMC_GD(4, 128, 2);
   } else {
-    if (KC == 256) DLLMC_GD(4, 256); else DLLMC_GD(4, 128);
+    if (KC == 256) DLLMC_GD(4, 256, 1); else DLLMC_GD(4, 128, 1);
   }
 #undef DLLMC_GD
   return true;

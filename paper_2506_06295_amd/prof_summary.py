@@ -3,7 +3,8 @@
     python -m paper_2506_06295_amd.prof_summary kernels <results.db>   # --kernel-trace runs
     python -m paper_2506_06295_amd.prof_summary pmc <results.db>       # --pmc runs
 
-`kernels` prints calls / total / average / min / max duration per kernel name and launch grid;
+`kernels` prints calls / total / average / min / max duration per kernel name and launch grid,
+then the idle time between consecutive dispatches (end of one kernel to start of the next);
 `pmc` prints the number of dispatches and the average counter value per kernel name and grid.
 """
 from __future__ import annotations
@@ -32,6 +33,16 @@ def kernels(db: str) -> None:
         print(f"{short(r[0]):64s} {grid:>20s} {r[4]:7d} {r[5] / 1e6:10.2f} {r[6] / 1e3:9.2f} "
               f"{r[7] / 1e3:9.2f} {r[8] / 1e3:9.2f} {100 * r[5] / total:6.2f}")
     print(f"total kernel time {total / 1e6:.2f} ms over {sum(r[4] for r in rows)} dispatches")
+    # idle time between back-to-back kernels of this library (gaps above 50 us are host pauses
+    # between steps or phases of the benchmark, not launch gaps, and are left out)
+    ev = c.execute("select start, end, name from kernels order by start").fetchall()
+    gaps = sorted((b[0] - a[1]) / 1e3 for a, b in zip(ev, ev[1:])
+                  if "dllmc" in a[2] and "dllmc" in b[2] and 0 <= b[0] - a[1] < 50_000)
+    if gaps:
+        n = len(gaps)
+        print(f"gap between consecutive kernels: n {n}, median {gaps[n // 2]:.2f} us, "
+              f"mean {sum(gaps) / n:.2f} us, p90 {gaps[(9 * n) // 10]:.2f} us, "
+              f"sum {sum(gaps) / 1e3:.2f} ms")
 
 
 def pmc(db: str) -> None:

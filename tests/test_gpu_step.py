@@ -23,6 +23,8 @@ MINI_DREAM = I.Config("mini_dream", T=2, d=896, H_q=7, H_kv=1, d_h=128, m=2432, 
 MINI_LONG = I.Config("mini_long", T=2, d=512, H_q=4, H_kv=4, d_h=128, m=1536, B=1, L_p=700,
                      L_r=130, steps=5, rho=0.1, K_p=4, K_r=3, dtype="bf16", vocab=4096)
 
+DEFAULT_NW_DUAL = 108  # the library's default shape of the fused gate/up kernel
+
 
 def run_schedule(cfg, stress=False, steps=None, **over):
     ws = I.all_weights(cfg)
@@ -82,6 +84,21 @@ def test_bf16_stress_schedule_exact_indices(cfg):
     assert st.worst_rel <= 2e-2
     assert st.worst_score_dev <= PU.score_tol(cfg)
     gpu.close()
+
+
+@pytest.mark.parametrize("nw_dual", [4, 8, 104, 108])
+@pytest.mark.parametrize("cfg", [MINI_LLADA, MINI_LONG], ids=lambda c: c.name)
+def test_fused_gate_up_kernel_variants(cfg, nw_dual):
+    """Every workgroup shape of the fused gate/up kernel (wavefronts per workgroup, one or two
+    wavefront groups over the contraction range) against the oracle."""
+    binding.set_gemm_tuning(nw_dual=nw_dual)
+    try:
+        gpu, ora, st = run_schedule(cfg.replace(steps=4), stress=True)
+        assert st.failed == 0, st.failures
+        assert st.worst_rel <= 2e-2
+        gpu.close()
+    finally:
+        binding.set_gemm_tuning(nw_dual=DEFAULT_NW_DUAL)
 
 
 @pytest.mark.parametrize("rho", [0.0, 0.05, 0.5, 1.0])
