@@ -120,6 +120,9 @@ enum {
   DLLMC_KC_GEMM_V = 0, DLLMC_KC_GEMM_QK, DLLMC_KC_GEMM_O, DLLMC_KC_GEMM_GATE_UP,
   DLLMC_KC_GEMM_DOWN, DLLMC_KC_ATTENTION, DLLMC_KC_SELECT, DLLMC_KC_ROW, DLLMC_KC_LISTS,
   DLLMC_KC_EVENT_OVERHEAD, /* an empty span per step: what one event record adds to a span */
+  DLLMC_KC_STREAM_KERNEL,  /* the launches of the five gemm classes that ran the weight-streaming
+                              kernel (k_gemm_stream), counted here a second time: one kernel's
+                              figures, comparable with a profiler's per-kernel average */
   DLLMC_NUM_KERNEL_CLASSES
 };
 typedef struct {

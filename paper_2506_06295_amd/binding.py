@@ -27,7 +27,7 @@ EXPORTS = (
     "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
     "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
 )
-NUM_KERNEL_CLASSES = 10
+NUM_KERNEL_CLASSES = 11
 
 
 class dllmc_model(C.Structure):

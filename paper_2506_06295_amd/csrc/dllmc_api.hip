@@ -107,7 +107,7 @@ struct dllmc_ctx {
 
   // optional per-kernel timing with HIP events on the context's stream
   bool profiling = false;
-  struct Span { hipEvent_t a, b; int cls; double bytes, flops; };
+  struct Span { hipEvent_t a, b; int cls; double bytes, flops; bool stream_kernel; };
   std::vector<Span> spans;           // recorded, not yet read back
   std::vector<hipEvent_t> free_events;
   std::vector<hipEvent_t> step_open_events;  // opening events of profiled steps, not yet recycled
@@ -146,7 +146,8 @@ struct Timed {
     hipEvent_t b = c->get_event();
     if (!b) return;
     (void)hipEventRecord(b, c->st);
-    c->spans.push_back({c->last_event, b, cls, bytes, flops});
+    const bool is_gemm = cls >= DLLMC_KC_GEMM_V && cls <= DLLMC_KC_GEMM_DOWN;
+    c->spans.push_back({c->last_event, b, cls, bytes, flops, is_gemm && gemm_last_was_stream()});
     c->last_event = b;
   }
 };
@@ -412,6 +413,13 @@ int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
     t.ms += ms;
     t.alg_bytes += sp.bytes;
     t.flops += sp.flops;
+    if (sp.stream_kernel) {
+      dllmc_kernel_stat& k = c->totals[DLLMC_KC_STREAM_KERNEL];
+      k.launches += 1;
+      k.ms += ms;
+      k.alg_bytes += sp.bytes;
+      k.flops += sp.flops;
+    }
     c->free_events.push_back(sp.b);  // sp.a is the previous span's b or a step's opening event
   }
   c->spans.clear();
@@ -426,7 +434,7 @@ int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
 const char* dllmc_kernel_class_name(int32_t cls) {
   static const char* names[DLLMC_NUM_KERNEL_CLASSES] = {
       "gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down", "attention", "select",
-      "row_kernels", "lists_and_copies", "event_overhead"};
+      "row_kernels", "lists_and_copies", "event_overhead", "k_gemm_stream"};
   return (cls >= 0 && cls < DLLMC_NUM_KERNEL_CLASSES) ? names[cls] : "?";
 }
 

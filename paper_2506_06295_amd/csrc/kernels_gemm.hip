@@ -483,6 +483,9 @@ bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const vo
 }
 }  // namespace
 
+static thread_local bool t_last_stream = false;
+bool gemm_last_was_stream() { return t_last_stream; }
+
 void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
 void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
 
@@ -575,10 +578,12 @@ int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity) 
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
                 const void* W1, int N0, int N, int K, float* c_part, size_t c_capacity,
                 hipStream_t st) {
+  t_last_stream = false;
   if (M <= 0 || N <= 0) return 1;
   const bool al = aligned16(A) && aligned16(W0) && (W1 == nullptr || aligned16(W1));
   const GemmPlan p = plan_gemm(dtype, al, lda, M, N, N0, K, c_capacity);
   if (p.kind == 0 || static_cast<size_t>(p.S) * M * N > c_capacity) return 0;  // nothing launched
+  t_last_stream = p.kind == 2;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(W0);
   const bf16_t* w1 = static_cast<const bf16_t*>(W1);
@@ -627,6 +632,7 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   const int BN = 16 * NW / KH;
   if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % BN == 0) || M > 128) return false;
   const dim3 grid(m / BN, (M + 63) / 64, 1);
+  t_last_stream = true;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
   const bf16_t* w1 = static_cast<const bf16_t*>(w_up);

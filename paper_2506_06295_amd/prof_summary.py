@@ -4,7 +4,7 @@
     python -m paper_2506_06295_amd.prof_summary pmc <results.db>       # --pmc runs
 
 `kernels` prints calls / total / average / min / max duration per kernel name and launch grid,
-then the idle time between consecutive dispatches (end of one kernel to start of the next);
+the totals per kernel over all grids, then the idle time between consecutive dispatches (end of one kernel to start of the next);
 `pmc` prints the number of dispatches and the average counter value per kernel name and grid.
 """
 from __future__ import annotations
@@ -33,6 +33,15 @@ def kernels(db: str) -> None:
         print(f"{short(r[0]):64s} {grid:>20s} {r[4]:7d} {r[5] / 1e6:10.2f} {r[6] / 1e3:9.2f} "
               f"{r[7] / 1e3:9.2f} {r[8] / 1e3:9.2f} {100 * r[5] / total:6.2f}")
     print(f"total kernel time {total / 1e6:.2f} ms over {sum(r[4] for r in rows)} dispatches")
+    # the same per kernel, all template arguments and grids together
+    fam = {}
+    for r in rows:
+        base = short(r[0]).split("<")[0].split("(")[0]
+        n, t = fam.get(base, (0, 0))
+        fam[base] = (n + r[4], t + r[5])
+    print()
+    for base, (n, t) in sorted(fam.items(), key=lambda kv: -kv[1][1])[:8]:
+        print(f"{base} over all grids: {n} launches, {t / 1e6:.2f} ms, average {t / n / 1e3:.2f} us per launch")
     # idle time between back-to-back kernels of this library (gaps above 50 us are host pauses
     # between steps or phases of the benchmark, not launch gaps, and are left out)
     ev = c.execute("select start, end, name from kernels order by start").fetchall()
