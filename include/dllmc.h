@@ -147,7 +147,7 @@ int dllmc_last_hip_error(void);
  * that each walk one half of the contraction range), force_s number of contraction slices
  * (0 = automatic), target_wg
  * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
- * from which the 128 x 128 tile kernel / the 256 x 256 LDS-direct kernel replaces the
+ * from which the 128 x 128 / the 256 x 256 LDS-direct tile kernel replaces the
  * weight-streaming kernel.  Results are
  * bit-reproducible for fixed settings; different settings change the float32 summation order
  * only. */

@@ -94,7 +94,7 @@ def test_select_rejects_bad_k():
     ("bf16", 20, 2432, 896, False),      # N = 19 * 128
     ("bf16", 40, 896, 2432, False),
     ("bf16", 17, 200, 72, True),         # falls back to the plain kernel
-    ("bf16", 256, 1024, 4096, True),     # 128 x 128 tile kernel, split contraction
+    ("bf16", 256, 1024, 4096, True),     # 128 x 128 LDS-direct kernel, split contraction
     ("bf16", 300, 512, 896, True),       # tile kernel, ragged last row tile, K = 14 * 64
     ("bf16", 768, 2432, 1024, False),    # tile kernel, N = 19 * 128
 ])
