@@ -16,7 +16,10 @@ datasets or trained weights are used):
                seeded-random still-masked positions receive seeded-random ids,
                so the response is fully unmasked when the schedule ends;
 * stress mode  additionally perturbs a seeded 30 % of response rows per step
-               with N(0, 0.5) noise so the selection boundary is decisive.
+               with N(0, 0.5) noise so the selection boundary is decisive;
+* closed loop  (the model's own predictions drive the unmasking): a token table of
+               vocab + 1 rows N(0, 1), the last row being [MASK], a final norm gain of 1 and
+               a vocabulary projection N(0, 0.02); the prompt ids are the schedule's.
 
 For bf16 configurations all values are rounded to the bf16 grid here (round to
 nearest even through torch's conversion) and handed out as float32 arrays.
@@ -58,6 +61,7 @@ class Config:
     dtype: str  # "f32" or "bf16": storage type of weights, activations and caches
     vocab: int
     unmask_per_step: int = 4
+    block_len: int = 0  # closed loop: positions per semi-autoregressive block (0 = L_r)
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
     seed: int = 20250606
@@ -193,6 +197,34 @@ class TokenSchedule:
             if cfg.dtype == "bf16":
                 out = to_bf16_grid(out)
         return out
+
+
+def head_weights(cfg: Config) -> Dict[str, np.ndarray]:
+    """Token table [vocab + 1, d] (last row: [MASK]), final norm gain [d], vocabulary
+    projection [vocab, d]; float32 arrays on the storage type's grid."""
+    e = _rng(cfg, 5).standard_normal((cfg.vocab + 1, cfg.d), dtype=np.float32)
+    w = 0.02 * _rng(cfg, 6).standard_normal((cfg.vocab, cfg.d), dtype=np.float32)
+    if cfg.dtype == "bf16":
+        e, w = to_bf16_grid(e), to_bf16_grid(w)
+    return {"embed": e, "final_norm_g": np.ones(cfg.d, dtype=np.float32), "lm_head": w}
+
+
+def initial_tokens(cfg: Config) -> np.ndarray:
+    """[B, n] token ids: the schedule's prompt, then an all-[MASK] response (id = vocab)."""
+    t = np.full((cfg.B, cfg.n), cfg.vocab, dtype=np.int64)
+    t[:, :cfg.L_p] = TokenSchedule(cfg).prompt_ids
+    return t
+
+
+def device_head_weights(cfg: Config, device: str = "cuda") -> Dict[str, torch.Tensor]:
+    """Same tensors as head_weights, drawn on `device` (full-size vocabularies)."""
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed + 77)
+    e = torch.randn((cfg.vocab + 1, cfg.d), dtype=torch.float32, device=device, generator=gen).to(dt)
+    w = (0.02 * torch.randn((cfg.vocab, cfg.d), dtype=torch.float32, device=device,
+                            generator=gen)).to(dt)
+    return {"embed": e, "final_norm_g": torch.ones(cfg.d, dtype=dt, device=device), "lm_head": w}
 
 
 def device_weights(cfg: Config, device: str = "cuda", n_layers: Optional[int] = None,
