@@ -141,6 +141,62 @@ const char* dllmc_strerror(int code);
 /* hipError_t value of the most recent failed HIP call in this process, 0 if none. */
 int dllmc_last_hip_error(void);
 
+/* ---- closed denoising loop around the cached step -------------------------------------
+ * Paper Sec. 3.1: the response starts fully masked; every step embeds the current tokens, runs
+ * the (cached) mask predictor, takes the greedy estimate of the clean sequence (per-position
+ * argmax) and applies the transition S of Eq. (transition_step).  S is low-confidence remasking
+ * (appendix "Experimental Details"): the response is cut into blocks of block_len positions
+ * completed left to right, steps / (L_r / block_len) steps per block; a step reveals, among the
+ * still masked positions of the current block, those whose greedy token has the highest softmax
+ * probability (equal probabilities: lower position first; equal logits: lower token id); the
+ * block's positions are spread evenly over its steps, the first block_len % steps_per_block
+ * steps reveal one more.  Revealed tokens never change.  The predictor's head is RMSNorm with
+ * final_norm_g followed by the vocabulary projection lm_head.
+ * All pointers are device pointers, borrowed for the life of the object.  Token ids are int32
+ * in [0, vocab]; vocab is the id of [MASK] and the index of its row in `embed`. */
+typedef struct {
+  const void* embed;        /* [vocab + 1, d_model], model dtype */
+  const void* final_norm_g; /* [d_model] */
+  const void* lm_head;      /* [vocab, d_model], row-major */
+  int32_t vocab;
+  int32_t steps;            /* denoising steps of one generation */
+  int32_t block_len;        /* 0 = L_r; must divide L_r, and L_r / block_len must divide steps */
+} dllmc_gen_config;
+typedef struct dllmc_gen dllmc_gen;
+
+/* Bytes of device workspace a generation loop on `ctx` needs (0: invalid arguments). */
+size_t dllmc_gen_workspace_bytes(const dllmc_ctx* ctx, const dllmc_gen_config* cfg);
+/* Creates the loop object on an existing context (whose stream it uses; the context must
+ * outlive it and must not be stepped by anyone else in between).  workspace: 256-byte aligned,
+ * caller-owned. */
+int dllmc_gen_create(dllmc_gen** out, dllmc_ctx* ctx, const dllmc_gen_config* cfg, void* workspace,
+                     size_t workspace_bytes);
+/* One step of the loop, enqueued on the context's stream: tokens [B, L_p + L_r] (in/out) are
+ * embedded, dllmc_step(step_idx) runs (sel_idx and n_sel as there, both may be null), the still
+ * masked positions of the current block get their greedy token and confidence, and
+ * *n_revealed (host, may be null) of them per sequence are revealed in `tokens`.  step_idx
+ * follows dllmc_step's rules and must be < steps.  `tokens` must be the state this loop
+ * produced (step 0: the whole response is [MASK]): the number of masked positions per block is
+ * taken from the schedule, not counted. */
+int dllmc_gen_step(dllmc_gen* gen, int32_t* tokens, int32_t step_idx, int32_t* sel_idx,
+                   int32_t* n_sel, int32_t* n_revealed);
+/* Results of the most recent dllmc_gen_step, copied on the stream (each destination may be
+ * null): x0 [B, L_r] greedy tokens and conf [B, L_r] their probabilities, valid at the positions
+ * that were masked inside the step's block (-1 / -inf elsewhere); chosen [B, L_r]: the first
+ * n_revealed entries of each row are the revealed positions, ascending; hidden_out
+ * [B, L_p + L_r, d_model] the step's output rows. */
+int dllmc_gen_read(dllmc_gen* gen, int32_t* x0, float* conf, int32_t* chosen, void* hidden_out);
+int dllmc_gen_destroy(dllmc_gen* gen);
+
+/* Head of the mask predictor as a single operation: for i < M, row r = rows[i] (i if rows is
+ * null) of hidden [*, d]: x0[i] = first argmax and conf[i] = softmax maximum of
+ * rmsnorm(hidden[r]) * final_norm_g projected by lm_head [vocab, d].  scratch: at least
+ * dllmc_op_head_scratch_bytes(dtype, M, vocab, d) bytes, 256-byte aligned. */
+size_t dllmc_op_head_scratch_bytes(int32_t dtype, int32_t M, int32_t vocab, int32_t d);
+int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_t M,
+                  const void* final_norm_g, float eps, const void* lm_head, int32_t vocab, int32_t d,
+                  void* scratch, int32_t* x0, float* conf, void* hip_stream);
+
 /* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
  * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
  * of the fused gate/up kernel (nw_dual + 100: the wavefronts of a workgroup form two groups

@@ -107,6 +107,8 @@ class GenReport:
     conf: np.ndarray      # [B, L_r] their confidences
     logit_gap: np.ndarray  # [B, L_r] best minus second-best logit
     chosen: List[np.ndarray]  # per sequence, ascending positions unmasked by this step
+    logits: List[np.ndarray]  # per sequence [L_r, vocab] (kept for near-tie checks at test sizes)
+    hidden_out: np.ndarray    # [B, n, d] output rows of the denoiser
     step_report: object
 
 
@@ -140,11 +142,12 @@ class Generator:
         conf = np.zeros((B, L_r))
         gap = np.zeros((B, L_r))
         new_tokens = tokens.copy()
-        chosen = []
+        chosen, all_logits = [], []
         for b in range(B):
             logits = head_logits(hidden_out[b, L_p:], self.final_norm_g, self.lm_head,
                                  den.model.rms_eps, den.storage)
             x0[b], conf[b] = greedy_with_confidence(logits)
+            all_logits.append(logits)
             top2 = np.partition(logits, -2, axis=-1)[:, -2:]
             gap[b] = top2[:, 1] - top2[:, 0]
             use_x0 = x0[b] if forced_x0 is None else np.asarray(forced_x0[b])
@@ -157,4 +160,6 @@ class Generator:
                                                      lo, hi, n_unmask)
             new_tokens[b, L_p:] = resp
             chosen.append(ch)
-        return new_tokens, GenReport(lo, hi, n_unmask, x0, conf, gap, chosen, rep)
+        return new_tokens, GenReport(lo=lo, hi=hi, n_unmask=n_unmask, x0=x0, conf=conf, logit_gap=gap,
+                                     chosen=chosen, logits=all_logits, hidden_out=hidden_out,
+                                     step_report=rep)

@@ -26,6 +26,8 @@ EXPORTS = (
     "dllmc_last_hip_error", "dllmc_op_select", "dllmc_op_vverify", "dllmc_op_linear",
     "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
     "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
+    "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
+    "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head",
 )
 NUM_KERNEL_CLASSES = 11
 
@@ -40,6 +42,11 @@ class dllmc_model(C.Structure):
 class dllmc_layer_weights(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g",
                                           "w_gate", "w_up", "w_down")]
+
+
+class dllmc_gen_config(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("final_norm_g", C.c_void_p), ("lm_head", C.c_void_p),
+                ("vocab", C.c_int32), ("steps", C.c_int32), ("block_len", C.c_int32)]
 
 
 class dllmc_kernel_stat(C.Structure):
@@ -94,6 +101,24 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.dllmc_op_attention_scratch_bytes.restype = C.c_size_t
+        L.dllmc_gen_workspace_bytes.restype = C.c_size_t
+        L.dllmc_gen_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(dllmc_gen_config)]
+        L.dllmc_gen_create.restype = C.c_int
+        L.dllmc_gen_create.argtypes = [C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(dllmc_gen_config),
+                                       C.c_void_p, C.c_size_t]
+        L.dllmc_gen_step.restype = C.c_int
+        L.dllmc_gen_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.dllmc_gen_read.restype = C.c_int
+        L.dllmc_gen_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dllmc_gen_destroy.restype = C.c_int
+        L.dllmc_gen_destroy.argtypes = [C.c_void_p]
+        L.dllmc_op_head_scratch_bytes.restype = C.c_size_t
+        L.dllmc_op_head_scratch_bytes.argtypes = [C.c_int32] * 4
+        L.dllmc_op_head.restype = C.c_int
+        L.dllmc_op_head.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_float,
+                                    C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]
         L.dllmc_op_attention_scratch_bytes.argtypes = []
         L.dllmc_profile_enable.restype = C.c_int
         L.dllmc_profile_enable.argtypes = [C.c_void_p, C.c_int32]
@@ -207,6 +232,84 @@ class CachedDenoiser:
             self.close()
         except Exception:
             pass
+
+
+class Generator:
+    """dllmc_gen_* around a CachedDenoiser: the closed denoising loop, tokens stay on the device."""
+
+    def __init__(self, den: CachedDenoiser, embed: torch.Tensor, final_norm_g: torch.Tensor,
+                 lm_head: torch.Tensor, steps: int, block_len: int = 0):
+        self._h = None
+        self.den = den
+        vocab = lm_head.shape[0]
+        for name, t, shape in (("embed", embed, (vocab + 1, den.d)), ("final_norm_g", final_norm_g, (den.d,)),
+                               ("lm_head", lm_head, (vocab, den.d))):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == den.torch_dtype and tuple(t.shape) == shape):
+                raise DllmcError(f"{name}: need a contiguous {den.torch_dtype} device tensor of shape {shape}")
+        self._keep = (embed, final_norm_g, lm_head)
+        self.vocab, self.steps = vocab, steps
+        self.cfg = dllmc_gen_config(embed.data_ptr(), final_norm_g.data_ptr(), lm_head.data_ptr(),
+                                    vocab, steps, block_len)
+        L = lib()
+        nbytes = L.dllmc_gen_workspace_bytes(den._h, C.byref(self.cfg))
+        if nbytes == 0:
+            raise DllmcError("dllmc_gen_workspace_bytes: invalid configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        _check(L.dllmc_gen_create(C.byref(h), den._h, C.byref(self.cfg), self.workspace.data_ptr(), nbytes),
+               "dllmc_gen_create")
+        self._h = h
+
+    def step(self, tokens: torch.Tensor, step_idx: int):
+        """Enqueue one step of the loop on tokens [B, n] int32 (updated in place); returns
+        (positions revealed per sequence, n_sel); den.sel_idx is filled as by den.step."""
+        den = self.den
+        if not (tokens.is_cuda and tokens.is_contiguous() and tokens.dtype == torch.int32
+                and tuple(tokens.shape) == (den.B, den.n)):
+            raise DllmcError("tokens must be a contiguous int32 [B, n] device tensor")
+        n_rev, n_sel = C.c_int32(0), C.c_int32(0)
+        _check(lib().dllmc_gen_step(self._h, tokens.data_ptr(), step_idx, den.sel_idx.data_ptr(),
+                                    C.byref(n_sel), C.byref(n_rev)), "dllmc_gen_step")
+        return n_rev.value, n_sel.value
+
+    def read(self, hidden: bool = False):
+        """(x0 [B, L_r] int32, conf [B, L_r] float32, chosen [B, L_r] int32[, hidden_out]) of the
+        most recent step."""
+        den = self.den
+        x0 = torch.empty((den.B, den.L_r), dtype=torch.int32, device="cuda")
+        conf = torch.empty((den.B, den.L_r), dtype=torch.float32, device="cuda")
+        chosen = torch.empty((den.B, den.L_r), dtype=torch.int32, device="cuda")
+        hout = torch.empty((den.B, den.n, den.d), dtype=den.torch_dtype, device="cuda") if hidden else None
+        _check(lib().dllmc_gen_read(self._h, x0.data_ptr(), conf.data_ptr(), chosen.data_ptr(), _ptr(hout)),
+               "dllmc_gen_read")
+        return (x0, conf, chosen, hout) if hidden else (x0, conf, chosen)
+
+    def close(self) -> None:
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib().dllmc_gen_destroy(h), "dllmc_gen_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def op_head(dtype: str, hidden: torch.Tensor, final_norm_g: torch.Tensor, lm_head: torch.Tensor,
+            eps: float, rows: Optional[torch.Tensor] = None):
+    """(x0 [M] int32, conf [M] float32) of the listed rows of hidden [*, d]."""
+    d = hidden.shape[1]
+    vocab = lm_head.shape[0]
+    M = hidden.shape[0] if rows is None else rows.numel()
+    code = _DTYPES[dtype][0]
+    scratch = torch.empty(lib().dllmc_op_head_scratch_bytes(code, M, vocab, d), dtype=torch.uint8, device="cuda")
+    x0 = torch.empty(M, dtype=torch.int32, device="cuda")
+    conf = torch.empty(M, dtype=torch.float32, device="cuda")
+    _check(lib().dllmc_op_head(code, hidden.data_ptr(), _ptr(rows), M, final_norm_g.data_ptr(), eps,
+                               lm_head.data_ptr(), vocab, d, scratch.data_ptr(), x0.data_ptr(),
+                               conf.data_ptr(), _stream_handle()), "dllmc_op_head")
+    return x0, conf
 
 
 def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1,

@@ -164,6 +164,27 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
 void launch_iota_rows(int* rows, int* inv, int B, int n, int first, int count, int per_seq,
                       int off, hipStream_t st);
 void launch_fill_i32(int* p, int value, size_t count, hipStream_t st);
+// ---- closed denoising loop (kernels_gen.hip) --------------------------------------------
+// out[r][:] = table[tokens[r]][:] for r < rows; table has vocab_rows rows of width d
+void launch_embed_gather(int dtype, const void* table, int vocab_rows, const int* tokens, int rows,
+                         int d, void* out, hipStream_t st);
+// elig[b][j] = 0 if response position j of sequence b holds mask_id and lo <= j < hi, else 1;
+// neg_conf[b][j] = +inf, x0[b][j] = -1.  tokens: [B, n].
+void launch_elig_scores(const int* tokens, int B, int n, int L_p, int lo, int hi, int mask_id,
+                        float* elig, float* neg_conf, int* x0, hipStream_t st);
+// z[i][:] = T(rmsnorm(hidden[rows[i]]) * gain) for i < M (rows == nullptr: identity)
+void launch_final_norm(int dtype, const void* hidden, const int* rows, int M, int d, float eps,
+                       const void* gain, void* z, hipStream_t st);
+// for i < M: token = first argmax of logits[i][0..vocab), p = softmax(logits[i])[token]; with
+// rows (rows[i] = b*n + L_p + j): x0[b][j] = token, conf[b][j] = sign * p; rows == nullptr:
+// x0[i], conf[i]
+void launch_head_finalize(const float* logits, int M, int vocab, const int* rows, int n, int L_p,
+                          float sign, int* x0, float* conf, hipStream_t st);
+void launch_negate_f32(float* p, size_t count, hipStream_t st);
+// tokens[b][L_p + chosen[b*chosen_stride + t]] = x0[b][...] for t < n_unmask
+void launch_apply_tokens(int* tokens, int B, int n, int L_p, const int* chosen, int chosen_stride,
+                         int n_unmask, const int* x0, hipStream_t st);
+
 // sel[r][j] = j for r < rows, j < L_r
 void launch_fill_sel_identity(int* sel, int rows, int L_r, hipStream_t st);
 

@@ -535,3 +535,196 @@ int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, cons
 }
 
 }  // extern "C"
+
+// ---- closed denoising loop ----------------------------------------------------------------
+
+namespace {
+struct GenLayout {
+  size_t off_hin, off_hout, off_z, off_logits, off_elig, off_negconf, off_x0, off_rows, off_chosen,
+      total;
+  size_t logits_floats;
+};
+
+bool gen_cfg_ok(const dllmc_ctx* c, const dllmc_gen_config* g) {
+  if (!c || !g || g->vocab < 1 || g->steps < 1 || g->block_len < 0) return false;
+  const int bl = g->block_len ? g->block_len : c->L_r;
+  if (bl > c->L_r || c->L_r % bl || g->steps % (c->L_r / bl)) return false;
+  return true;
+}
+
+GenLayout make_gen_layout(const dllmc_ctx* c, const dllmc_gen_config* g) {
+  GenLayout L{};
+  const size_t esz = c->lay.esz, B = c->m.batch, n = c->n, d = c->m.d_model, L_r = c->L_r;
+  const size_t bl = g->block_len ? g->block_len : c->L_r;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o += align_up(bytes, 256); return r; };
+  L.off_hin = take(B * n * d * esz);
+  L.off_hout = take(B * n * d * esz);
+  L.off_z = take(B * bl * d * esz);
+  L.logits_floats = B * bl * static_cast<size_t>(g->vocab);  // at most a block is masked per sequence
+  L.off_logits = take(L.logits_floats * sizeof(float));
+  L.off_elig = take(B * L_r * sizeof(float));
+  L.off_negconf = take(B * L_r * sizeof(float));
+  L.off_x0 = take(B * L_r * sizeof(int));
+  L.off_rows = take(B * L_r * sizeof(int));
+  L.off_chosen = take(B * L_r * sizeof(int));
+  L.total = o;
+  return L;
+}
+
+// positions a step reveals: the block's positions spread evenly over its steps, the remainder
+// to the first steps
+int reveal_count(int block_len, int steps_per_block, int t) {
+  return block_len / steps_per_block + (t < block_len % steps_per_block ? 1 : 0);
+}
+}  // namespace
+
+struct dllmc_gen {
+  dllmc_ctx* c;
+  dllmc_gen_config g;
+  GenLayout lay;
+  char* ws;
+  int block_len, steps_per_block;
+  int last_n_revealed;
+};
+
+extern "C" {
+
+size_t dllmc_gen_workspace_bytes(const dllmc_ctx* ctx, const dllmc_gen_config* cfg) {
+  if (!gen_cfg_ok(ctx, cfg)) return 0;
+  return make_gen_layout(ctx, cfg).total;
+}
+
+int dllmc_gen_create(dllmc_gen** out, dllmc_ctx* ctx, const dllmc_gen_config* cfg, void* workspace,
+                     size_t workspace_bytes) {
+  if (!out) return DLLMC_EINVAL;
+  *out = nullptr;
+  if (!gen_cfg_ok(ctx, cfg) || !workspace || !cfg->embed || !cfg->final_norm_g || !cfg->lm_head)
+    return DLLMC_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+      (reinterpret_cast<uintptr_t>(cfg->embed) & 15u) ||
+      (reinterpret_cast<uintptr_t>(cfg->lm_head) & 15u))
+    return DLLMC_EINVAL;
+  const GenLayout lay = make_gen_layout(ctx, cfg);
+  if (workspace_bytes < lay.total) return DLLMC_ENOMEM;
+  dllmc_gen* g = new (std::nothrow) dllmc_gen();
+  if (!g) return DLLMC_ENOMEM;
+  g->c = ctx;
+  g->g = *cfg;
+  g->lay = lay;
+  g->ws = static_cast<char*>(workspace);
+  g->block_len = cfg->block_len ? cfg->block_len : ctx->L_r;
+  g->steps_per_block = cfg->steps / (ctx->L_r / g->block_len);
+  g->last_n_revealed = 0;
+  *out = g;
+  return DLLMC_OK;
+}
+
+int dllmc_gen_step(dllmc_gen* g, int32_t* tokens, int32_t step_idx, int32_t* sel_idx,
+                   int32_t* n_sel, int32_t* n_revealed) {
+  if (!g || !tokens || step_idx < 0 || step_idx >= g->g.steps) return DLLMC_EINVAL;
+  dllmc_ctx* c = g->c;
+  const int B = c->m.batch, n = c->n, L_p = c->L_p, L_r = c->L_r, d = c->m.d_model, dt = c->m.dtype;
+  hipStream_t st = c->st;
+  void* hin = g->ws + g->lay.off_hin;
+  void* hout = g->ws + g->lay.off_hout;
+
+  // the step's block and how many of its positions are still masked / get revealed
+  const int blk = step_idx / g->steps_per_block, t = step_idx % g->steps_per_block;
+  const int lo = blk * g->block_len, hi = lo + g->block_len;
+  int masked = g->block_len;
+  for (int u = 0; u < t; ++u) masked -= reveal_count(g->block_len, g->steps_per_block, u);
+  const int n_rev = reveal_count(g->block_len, g->steps_per_block, t);
+  if (n_revealed) *n_revealed = n_rev;
+  g->last_n_revealed = n_rev;
+
+  (void)hipGetLastError();
+  launch_embed_gather(dt, g->g.embed, g->g.vocab + 1, tokens, B * n, d, hin, st);
+  const int rc = dllmc_step(c, hin, step_idx, hout, sel_idx, n_sel);
+  if (rc != DLLMC_OK) return rc;
+
+  float* elig = reinterpret_cast<float*>(g->ws + g->lay.off_elig);
+  float* negc = reinterpret_cast<float*>(g->ws + g->lay.off_negconf);
+  int* x0 = reinterpret_cast<int*>(g->ws + g->lay.off_x0);
+  int* rows = reinterpret_cast<int*>(g->ws + g->lay.off_rows);
+  int* chosen = reinterpret_cast<int*>(g->ws + g->lay.off_chosen);
+  launch_elig_scores(tokens, B, n, L_p, lo, hi, g->g.vocab, elig, negc, x0, st);
+  if (n_rev > 0) {
+    // the masked positions of the block, ascending: bottom-`masked` of a 0/1 score
+    launch_select(elig, B, L_r, masked, nullptr, 0, rows, masked, 0, nullptr, n, L_p, st);
+    const int M = B * masked;
+    void* z = g->ws + g->lay.off_z;
+    float* logits = reinterpret_cast<float*>(g->ws + g->lay.off_logits);
+    launch_final_norm(dt, hout, rows, M, d, c->m.rms_eps, g->g.final_norm_g, z, st);
+    // capacity of exactly one slice: the whole contraction in one pass, logits complete
+    const int S = launch_gemm(dt, z, d, nullptr, M, g->g.lm_head, nullptr, g->g.vocab, g->g.vocab, d,
+                              logits, static_cast<size_t>(M) * g->g.vocab, st);
+    if (S != 1) return DLLMC_ENOMEM;
+    launch_head_finalize(logits, M, g->g.vocab, rows, n, L_p, -1.0f, x0, negc, st);
+    // the n_rev most confident of them (lowest negated confidence, ties to the lower position)
+    launch_select(negc, B, L_r, n_rev, chosen, L_r, nullptr, 0, 0, nullptr, n, L_p, st);
+    launch_apply_tokens(tokens, B, n, L_p, chosen, L_r, n_rev, x0, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_gen_read(dllmc_gen* g, int32_t* x0, float* conf, int32_t* chosen, void* hidden_out) {
+  if (!g) return DLLMC_EINVAL;
+  dllmc_ctx* c = g->c;
+  const size_t BL = static_cast<size_t>(c->m.batch) * c->L_r;
+  hipStream_t st = c->st;
+  if (x0)
+    HIP_TRY(hipMemcpyAsync(x0, g->ws + g->lay.off_x0, BL * sizeof(int), hipMemcpyDeviceToDevice, st));
+  if (conf) {
+    // stored negated (selection key); the sign flips in place on the copy
+    HIP_TRY(hipMemcpyAsync(conf, g->ws + g->lay.off_negconf, BL * sizeof(float),
+                           hipMemcpyDeviceToDevice, st));
+    launch_negate_f32(conf, BL, st);
+  }
+  if (chosen)
+    HIP_TRY(hipMemcpyAsync(chosen, g->ws + g->lay.off_chosen, BL * sizeof(int),
+                           hipMemcpyDeviceToDevice, st));
+  if (hidden_out)
+    HIP_TRY(hipMemcpyAsync(hidden_out, g->ws + g->lay.off_hout,
+                           static_cast<size_t>(c->m.batch) * c->n * c->m.d_model * c->lay.esz,
+                           hipMemcpyDeviceToDevice, st));
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_gen_destroy(dllmc_gen* g) {
+  delete g;
+  return DLLMC_OK;
+}
+
+size_t dllmc_op_head_scratch_bytes(int32_t dtype, int32_t M, int32_t vocab, int32_t d) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || M < 1 || vocab < 1 || d < 1) return 0;
+  const size_t esz = dtype == DLLMC_BF16 ? 2 : 4;
+  return align_up(static_cast<size_t>(M) * d * esz, 256) +
+         align_up(static_cast<size_t>(M) * vocab * sizeof(float), 256);
+}
+
+int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_t M,
+                  const void* final_norm_g, float eps, const void* lm_head, int32_t vocab, int32_t d,
+                  void* scratch, int32_t* x0, float* conf, void* hip_stream) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !hidden || !final_norm_g || !lm_head ||
+      !scratch || !x0 || !conf || M < 1 || vocab < 1 || d < 1 ||
+      (reinterpret_cast<uintptr_t>(scratch) & 255u))
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t esz = dtype == DLLMC_BF16 ? 2 : 4;
+  void* z = scratch;
+  float* logits = reinterpret_cast<float*>(static_cast<char*>(scratch) +
+                                           align_up(static_cast<size_t>(M) * d * esz, 256));
+  launch_final_norm(dtype, hidden, rows, M, d, eps, final_norm_g, z, st);
+  const int S = launch_gemm(dtype, z, d, nullptr, M, lm_head, nullptr, vocab, vocab, d, logits,
+                            static_cast<size_t>(M) * vocab, st);
+  if (S != 1) return DLLMC_ENOMEM;
+  launch_head_finalize(logits, M, vocab, nullptr, 0, 0, 1.0f, x0, conf, st);
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+}  // extern "C"

@@ -28,16 +28,24 @@ constexpr int kMaxSlices = 8;
 // Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest), and each XCD has
 // its own L2.  With several row tiles per column tile, remap (blockIdx.x, blockIdx.y) so that
 // all row tiles of one column tile run back to back on the same XCD: the weight tile is then
-// fetched from HBM once and the other row tiles hit in that XCD's L2.
+// fetched from HBM once and the other row tiles hit in that XCD's L2.  The column tiles beyond
+// the last multiple of 8 are walked column by column after the remapped part.
 __device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
   const int nt = gridDim.x, mt = gridDim.y;
   col_tile = blockIdx.x;
   row_tile = blockIdx.y;
-  if (mt > 1 && (nt & 7) == 0) {
+  if (mt > 1 && nt >= 8) {
+    const int nt8 = nt & ~7;
     const int lin = blockIdx.x + nt * blockIdx.y;
-    const int xcd = lin & 7, slot = lin >> 3;
-    row_tile = slot % mt;
-    col_tile = (slot / mt) * 8 + xcd;
+    if (lin < nt8 * mt) {
+      const int xcd = lin & 7, slot = lin >> 3;
+      row_tile = slot % mt;
+      col_tile = (slot / mt) * 8 + xcd;
+    } else {
+      const int rest = lin - nt8 * mt;
+      row_tile = rest % mt;
+      col_tile = nt8 + rest / mt;
+    }
   }
 }
 int gemm_max_slices() { return kMaxSlices; }

@@ -89,10 +89,9 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.linalg.norm(got.astype(np.float64) - want) / max(np.linalg.norm(want), 1e-30))
 
 
-def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParityStats):
-    """One step on both sides; returns (gpu_out float64 ndarray, oracle_out)."""
-    out_t, n_sel = gpu.step(to_device(cfg, hidden_in), i)
-    torch.cuda.synchronize()
+def selection_checker(cfg, gpu, ora, i: int, n_sel: int, stats: ParityStats):
+    """After the GPU ran step i: checks the integer part of its selections and returns
+    (sel [T, B, n_sel], on_layer callback for the oracle's step) implementing the rule above."""
     sel = gpu.sel_idx[:, :, :n_sel].cpu().numpy().astype(np.int64)
     k = ora.k_sel
     tol = gap_tol(cfg)
@@ -134,7 +133,11 @@ def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParitySta
             stats.failures.append(f"step {i} layer {l} seq {b}: inadmissible set (gap {gap:.3e})")
         return got if (got.size == k and np.unique(got).size == k) else None
 
-    want, rep = ora.step(np.asarray(hidden_in, dtype=np.float64), i, on_layer=on_layer)
+    return sel, on_layer
+
+
+def check_selection_shape(cfg, ora, rep, sel, n_sel: int):
+    k = ora.k_sel
     if rep.response_refresh:
         assert n_sel == cfg.L_r
         assert np.array_equal(sel, np.broadcast_to(np.arange(cfg.L_r), sel.shape))
@@ -143,6 +146,15 @@ def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParitySta
         if k:
             assert np.all(np.diff(sel, axis=-1) > 0), "indices must be ascending"
             assert sel.min() >= 0 and sel.max() < cfg.L_r
+
+
+def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParityStats):
+    """One step on both sides; returns (gpu_out float64 ndarray, oracle_out)."""
+    out_t, n_sel = gpu.step(to_device(cfg, hidden_in), i)
+    torch.cuda.synchronize()
+    sel, on_layer = selection_checker(cfg, gpu, ora, i, n_sel, stats)
+    want, rep = ora.step(np.asarray(hidden_in, dtype=np.float64), i, on_layer=on_layer)
+    check_selection_shape(cfg, ora, rep, sel, n_sel)
     got = out_t.float().cpu().numpy().astype(np.float64)
     e = rel_err(got, want)
     stats.rel_per_step.append(e)
