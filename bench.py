@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for HBM counters)")
+    ap.add_argument("--no-closed-loop", action="store_true",
+                    help="skip the closed-loop generation leg (embedding, head, remasking)")
     ap.add_argument("--tune", default="", help="GEMM tuning knobs, e.g. nw=8,nw_dual=4,force_s=0,target_wg=256")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -253,6 +255,42 @@ def main():
         }
         if "ms_per_step_kind" in result and "adaptive" in result["ms_per_step_kind"]:
             result["uncached_gpu"]["speedup_adaptive_step"] = 1e3 * t_unc / result["ms_per_step_kind"]["adaptive"]
+
+    # the closed loop: the same schedule driven by the model's own predictions (embedding
+    # gather, cached step, mask-predictor head over the full vocabulary, remasking transition),
+    # tokens never leave the device
+    if not args.no_closed_loop:
+        from paper_2506_06295_amd.inputs import device_head_weights, initial_tokens
+        hw = device_head_weights(cfg)
+        gen = binding.Generator(den, hw["embed"], hw["final_norm_g"], hw["lm_head"], cfg.steps,
+                                cfg.block_len)
+        tok0 = torch.from_numpy(initial_tokens(cfg).astype(np.int32)).cuda()
+
+        def generation():
+            tok = tok0.clone()
+            for i in range(cfg.steps):
+                gen.step(tok, i)
+            return tok
+
+        generation()
+        torch.cuda.synchronize()
+        reps = max(1, min(3, (K + cfg.steps - 1) // cfg.steps))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            tok = generation()
+        torch.cuda.synchronize()
+        t_gen = (time.perf_counter() - t0) / reps
+        head_bytes = cfg.vocab * cfg.d * (4 if cfg.dtype == "f32" else 2)
+        result["closed_loop"] = {
+            "ms_per_generation": 1e3 * t_gen, "steps_per_s": cfg.steps / t_gen,
+            "response_tokens_per_s": cfg.B * cfg.L_r / t_gen,
+            "ms_per_step_beyond_core_path": 1e3 * (t_gen / cfg.steps - elapsed / K),
+            "vocab": cfg.vocab, "block_len": cfg.block_len or cfg.L_r,
+            "lm_head_bytes_per_step": head_bytes,
+            "all_revealed": bool((tok[:, cfg.L_p:] != cfg.vocab).all().item()),
+        }
+        gen.close()
+        del hw, gen
 
     den.close()
     if not args.no_cpu_baseline:

@@ -5,8 +5,8 @@ What it follows
 Sec. 3.1 (inference process of a diffusion LLM): the response starts fully masked; at every
 step the mask predictor gives a distribution over the clean sequence, the greedy estimate is
 the per-position argmax (Eq. for y-hat^(0|k)), and a transition function S (Eq.
-transition_step) produces the next state by "selectively updating tokens".  The appendix
-"Experimental Details" fixes what S is in the paper's runs: low-confidence remasking, with a
+transition_step) produces the next state by updating some of the tokens.  The appendix on
+experimental details fixes what S is in the paper's runs: low-confidence remasking, with a
 number of steps, a block length and a generation length per task (semi-autoregressive blocks
 when the block is shorter than the generation).
 

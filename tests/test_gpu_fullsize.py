@@ -124,3 +124,35 @@ def test_wide_shapes_properties_at_size(name, layers):
     v_ref = O.round_bf16(hs @ w0["wv"].T)
     assert PU.rel_err(v_gpu[sample], v_ref) < 1e-3
     unc.close()
+
+
+@pytest.mark.parametrize("name,M", [("llada8b", 256), ("llada8b", 4), ("dream7b", 100)])
+def test_head_at_full_vocabulary_sampled_rows(name, M):
+    """The mask-predictor head at the workload's vocabulary and width (126464 x 4096, 152064 x
+    3584): every row's greedy token and confidence from the GPU, the oracle on sampled rows."""
+    from oracle import dllm_generate_oracle as G
+    cfg = I.CONFIGS[name]
+    hw = I.device_head_weights(cfg)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(cfg.seed + M)
+    hidden = torch.randn((M + 5, cfg.d), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
+    rows = torch.randperm(M + 5, device="cuda", generator=g)[:M].to(torch.int32)
+    x0, conf = binding.op_head(cfg.dtype, hidden, hw["final_norm_g"], hw["lm_head"], cfg.rms_eps, rows)
+    torch.cuda.synchronize()
+    x0, conf = x0.cpu().numpy(), conf.cpu().numpy().astype(np.float64)
+    assert x0.min() >= 0 and x0.max() < cfg.vocab and np.all((conf > 0) & (conf <= 1))
+    sample = np.unique(np.linspace(0, M - 1, 6).astype(int))
+    hid = hidden.float().cpu().numpy()[rows.cpu().numpy()[sample]]
+    gain = hw["final_norm_g"].float().cpu().numpy()
+    logits = np.empty((sample.size, cfg.vocab))
+    for v0 in range(0, cfg.vocab, 16384):     # the projection in slabs: 16384 x d float64 at a time
+        w = hw["lm_head"][v0:v0 + 16384].float().cpu().numpy()
+        logits[:, v0:v0 + w.shape[0]] = G.head_logits(hid, gain, w, cfg.rms_eps, "bf16")
+    want_x0, want_conf = G.greedy_with_confidence(logits)
+    for t, i in enumerate(sample):
+        top = logits[t, want_x0[t]]
+        assert x0[i] == want_x0[t] or top - logits[t, x0[i]] <= 2e-3, f"row {i}"
+    assert np.allclose(conf[sample], want_conf, rtol=5e-3, atol=0), np.abs(conf[sample] / want_conf - 1).max()
+    print(f"\n[head {name} M={M}] sampled rows {sample.tolist()}: tokens equal "
+          f"{int(np.sum(x0[sample] == want_x0))}/{sample.size}, conf rel err "
+          f"{np.abs(conf[sample] / want_conf - 1).max():.2e}", flush=True)
