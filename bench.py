@@ -200,6 +200,8 @@ def main():
         # the dominant kernel: every launch of the weight-streaming GEMM kernel (the library
         # counts those launches a second time under their kernel's name)
         ks = stats.pop("k_gemm_stream")
+        stats.pop("head_gemm", None)   # closed-loop classes: empty in this pass
+        stats.pop("gen_other", None)
         gemm = [stats[k] for k in ("gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down")]
         total_ms = sum(v["ms"] for v in stats.values())
         k_ms, k_n = ks["ms"], max(ks["launches"], 1)
@@ -289,6 +291,20 @@ def main():
             "lm_head_bytes_per_step": head_bytes,
             "all_revealed": bool((tok[:, cfg.L_p:] != cfg.vocab).all().item()),
         }
+        if not args.no_profile:
+            # one generation with events: the vocabulary projection on its own
+            den.profile_enable(True)
+            generation()
+            gst = den.profile_read(reset=True)
+            den.profile_enable(False)
+            hg, go = gst["head_gemm"], gst["gen_other"]
+            h_ms = max(hg["ms"] - result["roofline"]["event_overhead_us"] * 1e-3 * hg["launches"], 1e-9)
+            result["closed_loop"]["head_gemm"] = {
+                "launches": hg["launches"], "avg_us": 1e3 * h_ms / max(hg["launches"], 1),
+                "GBps": hg["alg_bytes"] / (h_ms * 1e-3) / 1e9,
+                "hbm_frac": hg["alg_bytes"] / (h_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "TFLOPs": hg["flops"] / (h_ms * 1e-3) / 1e12}
+            result["closed_loop"]["other_kernels_ms_per_step"] = go["ms"] / cfg.steps
         gen.close()
         del hw, gen
 

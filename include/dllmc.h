@@ -123,6 +123,10 @@ enum {
   DLLMC_KC_STREAM_KERNEL,  /* the launches of the five gemm classes that ran the weight-streaming
                               kernel (k_gemm_stream), counted here a second time: one kernel's
                               figures, comparable with a profiler's per-kernel average */
+  DLLMC_KC_HEAD_GEMM,      /* closed loop: vocabulary projection of the masked rows */
+  DLLMC_KC_GEN_OTHER,      /* closed loop: final norm, greedy token + confidence, eligibility,
+                              the two selections, token update (the embedding gather runs before
+                              the step's first event and is not timed) */
   DLLMC_NUM_KERNEL_CLASSES
 };
 typedef struct {

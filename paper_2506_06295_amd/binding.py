@@ -29,7 +29,7 @@ EXPORTS = (
     "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
     "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head",
 )
-NUM_KERNEL_CLASSES = 11
+NUM_KERNEL_CLASSES = 13
 
 
 class dllmc_model(C.Structure):

@@ -146,7 +146,7 @@ struct Timed {
     hipEvent_t b = c->get_event();
     if (!b) return;
     (void)hipEventRecord(b, c->st);
-    const bool is_gemm = cls >= DLLMC_KC_GEMM_V && cls <= DLLMC_KC_GEMM_DOWN;
+    const bool is_gemm = (cls >= DLLMC_KC_GEMM_V && cls <= DLLMC_KC_GEMM_DOWN) || cls == DLLMC_KC_HEAD_GEMM;
     c->spans.push_back({c->last_event, b, cls, bytes, flops, is_gemm && gemm_last_was_stream()});
     c->last_event = b;
   }
@@ -434,7 +434,8 @@ int dllmc_profile_read(dllmc_ctx* c, dllmc_kernel_stat* out, int32_t reset) {
 const char* dllmc_kernel_class_name(int32_t cls) {
   static const char* names[DLLMC_NUM_KERNEL_CLASSES] = {
       "gemm_v", "gemm_qk", "gemm_o", "gemm_gate_up", "gemm_down", "attention", "select",
-      "row_kernels", "lists_and_copies", "event_overhead", "k_gemm_stream"};
+      "row_kernels", "lists_and_copies", "event_overhead", "k_gemm_stream", "head_gemm",
+      "gen_other"};
   return (cls >= 0 && cls < DLLMC_NUM_KERNEL_CLASSES) ? names[cls] : "?";
 }
 
@@ -648,22 +649,37 @@ int dllmc_gen_step(dllmc_gen* g, int32_t* tokens, int32_t step_idx, int32_t* sel
   int* x0 = reinterpret_cast<int*>(g->ws + g->lay.off_x0);
   int* rows = reinterpret_cast<int*>(g->ws + g->lay.off_rows);
   int* chosen = reinterpret_cast<int*>(g->ws + g->lay.off_chosen);
-  launch_elig_scores(tokens, B, n, L_p, lo, hi, g->g.vocab, elig, negc, x0, st);
+  const double esz = static_cast<double>(c->lay.esz);
+  {
+    Timed tm(c, DLLMC_KC_GEN_OTHER, B * L_r * 16.0, 0);
+    launch_elig_scores(tokens, B, n, L_p, lo, hi, g->g.vocab, elig, negc, x0, st);
+  }
   if (n_rev > 0) {
-    // the masked positions of the block, ascending: bottom-`masked` of a 0/1 score
-    launch_select(elig, B, L_r, masked, nullptr, 0, rows, masked, 0, nullptr, n, L_p, st);
     const int M = B * masked;
+    const double V = g->g.vocab;
     void* z = g->ws + g->lay.off_z;
     float* logits = reinterpret_cast<float*>(g->ws + g->lay.off_logits);
-    launch_final_norm(dt, hout, rows, M, d, c->m.rms_eps, g->g.final_norm_g, z, st);
-    // capacity of exactly one slice: the whole contraction in one pass, logits complete
-    const int S = launch_gemm(dt, z, d, nullptr, M, g->g.lm_head, nullptr, g->g.vocab, g->g.vocab, d,
-                              logits, static_cast<size_t>(M) * g->g.vocab, st);
-    if (S != 1) return DLLMC_ENOMEM;
-    launch_head_finalize(logits, M, g->g.vocab, rows, n, L_p, -1.0f, x0, negc, st);
-    // the n_rev most confident of them (lowest negated confidence, ties to the lower position)
-    launch_select(negc, B, L_r, n_rev, chosen, L_r, nullptr, 0, 0, nullptr, n, L_p, st);
-    launch_apply_tokens(tokens, B, n, L_p, chosen, L_r, n_rev, x0, st);
+    {
+      // the masked positions of the block, ascending: bottom-`masked` of a 0/1 score
+      Timed tm(c, DLLMC_KC_GEN_OTHER, B * L_r * 4.0 + M * (4.0 + 2.0 * d * esz), 0);
+      launch_select(elig, B, L_r, masked, nullptr, 0, rows, masked, 0, nullptr, n, L_p, st);
+      launch_final_norm(dt, hout, rows, M, d, c->m.rms_eps, g->g.final_norm_g, z, st);
+    }
+    {
+      // capacity of exactly one slice: the whole contraction in one pass, logits complete
+      Timed tm(c, DLLMC_KC_HEAD_GEMM, (V * d + static_cast<double>(M) * d) * esz + M * V * 4.0,
+               2.0 * M * V * d);
+      const int S = launch_gemm(dt, z, d, nullptr, M, g->g.lm_head, nullptr, g->g.vocab, g->g.vocab,
+                                d, logits, static_cast<size_t>(M) * g->g.vocab, st);
+      if (S != 1) return DLLMC_ENOMEM;
+    }
+    {
+      Timed tm(c, DLLMC_KC_GEN_OTHER, M * V * 4.0 + B * L_r * 8.0, 0);
+      launch_head_finalize(logits, M, g->g.vocab, rows, n, L_p, -1.0f, x0, negc, st);
+      // the n_rev most confident (lowest negated confidence, ties to the lower position)
+      launch_select(negc, B, L_r, n_rev, chosen, L_r, nullptr, 0, 0, nullptr, n, L_p, st);
+      launch_apply_tokens(tokens, B, n, L_p, chosen, L_r, n_rev, x0, st);
+    }
   }
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;
