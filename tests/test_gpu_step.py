@@ -101,6 +101,20 @@ def test_fused_gate_up_kernel_variants(cfg, nw_dual):
         binding.set_gemm_tuning(nw_dual=DEFAULT_NW_DUAL)
 
 
+@pytest.mark.parametrize("cfg", [I.CONFIGS["toy"].replace(L_p=0, K_p=3), MINI_LLADA.replace(L_p=0, steps=5),
+                                 MINI_LLADA.replace(B=3, L_p=33, L_r=47, steps=5)],
+                         ids=["toy_no_prompt", "mini_no_prompt", "mini_odd_batch_and_lengths"])
+def test_degenerate_shapes(cfg):
+    """No prompt at all (every prompt-side list is empty) and odd batch / lengths that leave
+    ragged row tiles everywhere."""
+    gpu, ora, st = run_schedule(cfg, stress=True)
+    report(cfg.name, st)
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+    PU.compare_caches(cfg, gpu, ora, 1e-4 if cfg.dtype == "f32" else 2e-2)
+    gpu.close()
+
+
 @pytest.mark.parametrize("rho", [0.0, 0.05, 0.5, 1.0])
 def test_rho_sweep_bf16(rho):
     cfg = MINI_LLADA.replace(steps=4)
