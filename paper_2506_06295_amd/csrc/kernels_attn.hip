@@ -72,6 +72,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const T* __restrict__ q, int
 constexpr int kDH = 128;       // head width of the MFMA kernel
 constexpr int kVtStride = 40;  // 32 keys + 8 pad (bf16 elements) per transposed V row
 constexpr int kQT = 64;        // queries per workgroup: four wavefronts x 16
+constexpr int kPreload = 3;    // key ranges of up to this many 32-key blocks are fetched whole
 constexpr int kMaxKeySplit = 8;
 
 // Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; blockIdx.z
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
                                                    int H_kv, int KS, bf16_t* __restrict__ out,
                                                    float* __restrict__ part) {
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][kDH * kVtStride];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[kPreload][kDH * kVtStride];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int a = blockIdx.y;
@@ -149,24 +150,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     }
   };
 
-  uint4 vraw[2];
-  bf16x8 kf[2][4];
-  if (blk0 < blk1) {
-    load_v(blk0, vraw);
-    load_k(blk0, kf);
-    store_v(Vt[0], vraw);
-  }
-  __syncthreads();
-
-  for (int blk = blk0; blk < blk1; ++blk) {
-    const int cur = (blk - blk0) & 1;
-    const bool more = blk + 1 < blk1;
-    bf16x8 kn[2][4];
-    if (more) {
-      load_v(blk + 1, vraw);
-      load_k(blk + 1, kn);
-    }
-    const int key0 = blk * 32;
+  // One 32-key block: scores S^T = K Q^T, running softmax, O^T += V^T P^T.
+  auto process = [&](const bf16x8 (&kf)[2][4], const bf16_t* vt, int key0) {
     // scores of the two 16-key halves: S^T[key][query]
     f32x4 st[2];
 #pragma unroll
@@ -216,7 +201,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
       o_acc[db][3] *= alpha;
     }
     // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
-    const bf16_t* vt = Vt[cur];
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       const bf16_t* vr = vt + (db * 16 + ln) * kVtStride + 4 * lg;
@@ -227,14 +211,52 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
       o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[db], 0, 0, 0);
       o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o_acc[db], 0, 0, 0);
     }
-    if (more) {
-      store_v(Vt[cur ^ 1], vraw);
+  };
+
+  const int nb = blk1 - blk0;
+  if (nb > 0 && nb <= kPreload) {
+    // Short key range (split keys of an adaptive step): every K fragment and V tile of the
+    // range is requested before the first one is used, so the range costs one trip to memory
+    // instead of one per block.
+    bf16x8 kall[kPreload][2][4];
+    uint4 vall[kPreload][2];
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) kf[sb][c] = kn[sb][c];
+    for (int j = 0; j < kPreload; ++j) {
+      const int blk = min(blk0 + j, blk1 - 1);  // blocks past the range repeat the last one, unused
+      load_k(blk, kall[j]);
+      load_v(blk, vall[j]);
     }
+#pragma unroll
+    for (int j = 0; j < kPreload; ++j) store_v(Vt[j], vall[j]);
     __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kPreload; ++j)
+      if (j < nb) process(kall[j], Vt[j], (blk0 + j) * 32);
+  } else if (nb > 0) {
+    uint4 vraw[2];
+    bf16x8 kf[2][4];
+    load_v(blk0, vraw);
+    load_k(blk0, kf);
+    store_v(Vt[0], vraw);
+    __syncthreads();
+    for (int blk = blk0; blk < blk1; ++blk) {
+      const int cur = (blk - blk0) & 1;
+      const bool more = blk + 1 < blk1;
+      bf16x8 kn[2][4];
+      if (more) {
+        load_v(blk + 1, vraw);
+        load_k(blk + 1, kn);
+      }
+      process(kf, Vt[cur], blk * 32);
+      if (more) {
+        store_v(Vt[cur ^ 1], vraw);
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) kf[sb][c] = kn[sb][c];
+      }
+      __syncthreads();
+    }
   }
 
   l_run += __shfl_xor(l_run, 16, 64);
