@@ -156,3 +156,34 @@ def test_head_at_full_vocabulary_sampled_rows(name, M):
     print(f"\n[head {name} M={M}] sampled rows {sample.tolist()}: tokens equal "
           f"{int(np.sum(x0[sample] == want_x0))}/{sample.size}, conf rel err "
           f"{np.abs(conf[sample] / want_conf - 1).max():.2e}", flush=True)
+
+
+def test_llada8b_closed_loop_first_steps_match_oracle():
+    """The closed loop at the headline size (32 layers, vocabulary 126464): a full-refresh step
+    and an adaptive step driven by the model's own predictions, every decision checked by
+    tests/test_gpu_generate.run_loop's rules against the oracle."""
+    from oracle import dllm_generate_oracle as G
+    from tests.test_gpu_generate import run_loop
+    cfg = I.CONFIGS["llada8b"]
+    floor = noise_floor()
+    t0 = time.time()
+    dev_w = I.device_weights(cfg)
+    host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]
+    hw = I.device_head_weights(cfg)
+    host_hw = {k: v.float().cpu().numpy() for k, v in hw.items()}
+    print(f"\n[fullsize loop] weights ready {time.time() - t0:.1f}s", flush=True)
+    gpu = make_gpu(cfg, dev_w)
+    ora = O.CachedDenoiser(PU.oracle_model(cfg), host_w, cfg.B, cfg.L_p, cfg.L_r, cfg.rho, cfg.K_p,
+                           cfg.K_r, storage="bf16")
+    ggen = binding.Generator(gpu, hw["embed"], hw["final_norm_g"], hw["lm_head"], cfg.steps)
+    ogen = G.Generator(ora, host_hw["embed"], host_hw["final_norm_g"], host_hw["lm_head"], cfg.vocab,
+                       cfg.steps)
+    st, tally, tokens = run_loop(cfg, steps=2, loop=(gpu, ora, ggen, ogen),
+                                 act_tol=max(2e-2, 1.25 * floor["hidden_out"]))
+    print(f"[fullsize loop] rel {st.worst_rel:.3e} {tally} selection exact/tied/followed/failed "
+          f"{st.exact}/{st.tied_same}/{st.followed}/{st.failed}  t={time.time() - t0:.1f}s", flush=True)
+    assert st.failed == 0, st.failures
+    assert tally["tokens_exact"] > 0
+    assert int(np.sum(tokens[:, cfg.L_p:] != cfg.vocab)) == 2 * cfg.B * (cfg.L_r // cfg.steps)
+    ggen.close()
+    gpu.close()
