@@ -152,6 +152,38 @@ def cosine_scores(v_new: np.ndarray, v_old: np.ndarray) -> np.ndarray:
     return dot / np.maximum(den, 1e-8)
 
 
+def l2_scores(v_new: np.ndarray, v_old: np.ndarray) -> np.ndarray:
+    """Score of the L2-distance variant of V-verify (appendix "Impact of Similarity Metric"):
+    minus the Euclidean distance between the current and the cached Value row, so that, as with
+    the cosine, the lowest scores mark the rows that changed most."""
+    diff = v_new - v_old
+    return -np.sqrt(np.sum(diff * diff, axis=1))
+
+
+def _fmix32(x: int) -> int:
+    """Finalizer of MurmurHash3 (32-bit): a bijective avalanche mix."""
+    x &= 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+    x ^= x >> 13
+    x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def random_scores(seed: int, step: int, layer: int, seq: int, L_r: int) -> np.ndarray:
+    """Scores of the random-selection baseline (Sec. 4.3, selection strategies): a counter-based
+    uniform in [0, 1) per (seed, step, layer, sequence, position), 24 bits, exactly representable
+    in float32.  h = seed; for each of step, layer, sequence, position: h = fmix32(h xor value)."""
+    out = np.empty(L_r, dtype=np.float64)
+    h0 = seed & 0xFFFFFFFF
+    for v in (step, layer, seq):
+        h0 = _fmix32(h0 ^ (v & 0xFFFFFFFF))
+    for j in range(L_r):
+        out[j] = (_fmix32(h0 ^ j) >> 8) * 2.0 ** -24
+    return out
+
+
 def num_selected(rho: float, L_r: int) -> int:
     """floor(rho * |y|) with |y| the response length (Sec. 3.2.2)."""
     return int(math.floor(float(rho) * L_r + 1e-6))
@@ -242,9 +274,19 @@ class CachedDenoiser:
 
     def __init__(self, model: Model, weights: Sequence[Dict[str, np.ndarray]], B: int,
                  L_p: int, L_r: int, rho: float, K_p: int, K_r: int,
-                 storage: str = "f64", dtype=np.float64):
+                 storage: str = "f64", dtype=np.float64, metric: str = "cosine",
+                 selection: str = "verify", v_update: str = "all", seed: int = 0):
+        """metric / selection / v_update pick the variants the paper compares with its default
+        (cosine V-verify, whole-V overwrite): metric "l2" (appendix "Impact of Similarity
+        Metric"), selection "random" (Sec. 4.3), v_update "selected" (appendix "Design Choice
+        Between Full V-Cache Overwrite and Selective Update": only the selected rows' Values
+        are written back, the others keep the cached ones)."""
         if not (0.0 <= rho <= 1.0) or K_p < 1 or K_r < 1:
             raise ValueError("need 0 <= rho <= 1 and K_p, K_r >= 1")
+        if metric not in ("cosine", "l2") or selection not in ("verify", "random") or \
+                v_update not in ("all", "selected"):
+            raise ValueError("unknown policy")
+        self.metric, self.selection, self.v_update, self.seed = metric, selection, v_update, seed
         self.model, self.weights = model, weights
         self.B, self.L_p, self.L_r, self.n = B, L_p, L_r, L_p + L_r
         self.rho, self.K_p, self.K_r = rho, K_p, K_r
@@ -302,7 +344,12 @@ class CachedDenoiser:
                 if Rf:
                     S = np.arange(L_r)
                 else:
-                    s = cosine_scores(V_new[resp_in_C], self.V[l][b, L_p:])
+                    if self.selection == "random":
+                        s = random_scores(self.seed, i, l, b, L_r)
+                    elif self.metric == "l2":
+                        s = l2_scores(V_new[resp_in_C], self.V[l][b, L_p:])
+                    else:
+                        s = cosine_scores(V_new[resp_in_C], self.V[l][b, L_p:])
                     S = bottom_k(s, self.k_sel)
                     rep.scores[l][b] = s
                     rep.gaps[l][b] = boundary_gap(s, self.k_sel)
@@ -313,8 +360,14 @@ class CachedDenoiser:
                     if forced_sel is not None:
                         S = np.sort(np.asarray(forced_sel[l][b], dtype=np.int64))
                 rep.selected[l][b] = S
-                # the whole response V (and the prompt V on a prompt refresh) is overwritten
-                self.V[l][b, C] = V_new
+                if self.v_update == "all" or Rf:
+                    # the whole response V (and the prompt V on a prompt refresh) is overwritten
+                    self.V[l][b, C] = V_new
+                else:
+                    # variant: only the selected rows (and a refreshed prompt) take their new Values
+                    upd = np.concatenate([np.arange(L_p) if P else np.zeros(0, dtype=np.int64),
+                                          L_p + S]).astype(np.int64)
+                    self.V[l][b, upd] = V_new[upd - off]
                 # rows whose K / AttnOut / FFNOut are recomputed
                 R = np.concatenate([np.arange(L_p) if P else np.zeros(0, dtype=np.int64),
                                     L_p + S]).astype(np.int64)
