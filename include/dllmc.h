@@ -87,6 +87,20 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
 /* floor(rho * L_r): rows recomputed per sequence and layer on an adaptive step (Sec. 3.2.2). */
 int32_t dllmc_num_selected(const dllmc_ctx* ctx);
 
+/* Variants the paper compares with its default (cosine V-verify with whole-V overwrite);
+ * take effect at the next dllmc_step, normally set before step 0.
+ *   metric     0: cosine of Eq. (cos_sim); 1: minus the Euclidean distance between the current
+ *              and the cached Value row (appendix "Impact of Similarity Metric")
+ *   selection  0: the floor(rho*L_r) lowest scores; 1: random rows (Sec. 4.3): the scores are
+ *              24-bit uniforms h >> 8 scaled by 2^-24, h = seed, then for each of step_idx,
+ *              layer, sequence, position: h = fmix32(h xor value), fmix32 being the 32-bit
+ *              finalizer of MurmurHash3; dllmc_read_scores returns them
+ *   v_update   0: the whole response V is overwritten on an adaptive step; 1: only the selected
+ *              rows' Values are written back (appendix "Design Choice Between Full V-Cache
+ *              Overwrite and Selective Update") */
+int dllmc_set_policy(dllmc_ctx* ctx, int32_t metric, int32_t selection, int32_t v_update,
+                     uint32_t seed);
+
 /* One denoising step (Sec. 3.2 "Iterative Steps").
  *   hidden_in  device [B, L_p+L_r, d], model dtype: embedded tokens of this step.
  *   step_idx   0 for the first call (fills both caches), then strictly increasing; passing 0

@@ -27,7 +27,7 @@ EXPORTS = (
     "dllmc_op_attention", "dllmc_profile_enable", "dllmc_profile_read", "dllmc_kernel_class_name",
     "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
     "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
-    "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head",
+    "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head", "dllmc_set_policy",
 )
 NUM_KERNEL_CLASSES = 13
 
@@ -101,6 +101,8 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.dllmc_op_attention_scratch_bytes.restype = C.c_size_t
+        L.dllmc_set_policy.restype = C.c_int
+        L.dllmc_set_policy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
         L.dllmc_gen_workspace_bytes.restype = C.c_size_t
         L.dllmc_gen_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(dllmc_gen_config)]
         L.dllmc_gen_create.restype = C.c_int
@@ -200,6 +202,14 @@ class CachedDenoiser:
         _check(lib().dllmc_step(self._h, hidden_in.data_ptr(), step_idx, hidden_out.data_ptr(),
                                 self.sel_idx.data_ptr(), C.byref(n_sel)), "dllmc_step")
         return hidden_out, n_sel.value
+
+    def set_policy(self, metric: str = "cosine", selection: str = "verify", v_update: str = "all",
+                   seed: int = 0) -> None:
+        """Variants of the paper's ablations; see dllmc_set_policy."""
+        _check(lib().dllmc_set_policy(self._h, {"cosine": 0, "l2": 1}[metric],
+                                      {"verify": 0, "random": 1}[selection],
+                                      {"all": 0, "selected": 1}[v_update], seed & 0xFFFFFFFF),
+               "dllmc_set_policy")
 
     def read_cache(self, layer: int, which: int) -> torch.Tensor:
         width = self.d_kv if which < 2 else self.d

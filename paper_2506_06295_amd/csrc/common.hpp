@@ -105,10 +105,20 @@ void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int*
                        const void* gain, float* x, void* h, hipStream_t st);
 
 // V finalize: for i < M: row = rows[i] (i if rows == nullptr); v = T(sum_s c_part[s][i][:]);
-// if score != nullptr and row is a response row: score[seq][j] = cos(v, v_cache[row]);
-// v_cache[row] = v.
+// if score != nullptr and row is a response row: score[seq][j] = cos(v, v_cache[row]) (metric
+// 0) or -|v - v_cache[row]| (metric 1); then v_cache[row] = v, except that response rows go
+// to v_stage[i] instead when v_stage != nullptr (selected-only update, see launch_scatter_v).
 void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
-                       int d_kv, void* v_cache, float* score, hipStream_t st);
+                       int d_kv, void* v_cache, float* score, int metric, void* v_stage,
+                       hipStream_t st);
+// v_cache[row] = v_stage[(row / n) * carried_per_seq + row % n - first] for the response rows
+// among rows_R[0..M_R)
+void launch_scatter_v(const RowKernelArgs& a, const int* rows_R, int M_R, int first,
+                      int carried_per_seq, int d_kv, const void* v_stage, void* v_cache,
+                      hipStream_t st);
+// score[b][j] = 24-bit uniform in [0, 1) keyed by (seed, step, layer, b, j)
+void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, float* out,
+                          hipStream_t st);
 
 // Q/K finalize: for i < M: row = rows[i], pos = row % n; c = sum_s c_part[s][i][0..d_q+d_kv);
 // q_out[i] = T(rope(c[0..d_q))), k_cache[row] = T(rope(c[d_q..))).  rope_tab[pos][t] =

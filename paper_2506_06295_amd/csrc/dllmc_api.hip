@@ -104,6 +104,11 @@ struct dllmc_ctx {
   Layout lay;
   char* ws;
   bool have_scores;
+  // variants of the paper's ablations (dllmc_set_policy); defaults are the paper's method
+  int metric = 0;          // 0 cosine, 1 minus L2 distance
+  bool random_sel = false;
+  bool v_selected_only = false;
+  uint32_t seed = 0;
 
   // optional per-kernel timing with HIP events on the context's stream
   bool profiling = false;
@@ -221,6 +226,17 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
 
 int32_t dllmc_num_selected(const dllmc_ctx* ctx) { return ctx ? ctx->k_sel : DLLMC_EINVAL; }
 
+int dllmc_set_policy(dllmc_ctx* c, int32_t metric, int32_t selection, int32_t v_update,
+                     uint32_t seed) {
+  if (!c || metric < 0 || metric > 1 || selection < 0 || selection > 1 || v_update < 0 || v_update > 1)
+    return DLLMC_EINVAL;
+  c->metric = metric;
+  c->random_sel = selection == 1;
+  c->v_selected_only = v_update == 1;
+  c->seed = seed;
+  return DLLMC_OK;
+}
+
 int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidden_out,
                int32_t* sel_idx, int32_t* n_sel) {
   if (!c || !hidden_in || !hidden_out || step_idx < 0) return DLLMC_EINVAL;
@@ -301,15 +317,22 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       if (S == 0) return DLLMC_ENOMEM;
     }
     float* sc = scores + static_cast<size_t>(l) * B * L_r;
+    // selected-only V update: the response rows' new Values wait in the attention output
+    // buffer (free until this layer's attention) for the selection
+    const bool defer_v = c->v_selected_only && !Rf;
     {
       Timed t(c, DLLMC_KC_ROW, Mc * d_kv * (4.0 + 2.0 * esz), 0);
-      launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, Rf ? nullptr : sc, st);
+      launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, (Rf || c->random_sel) ? nullptr : sc,
+                        c->metric, defer_v ? abuf : nullptr, st);
     }
     if (!Rf) {
       Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + c->k_sel * 8.0 + L_r * 4.0), 0);
+      if (c->random_sel) launch_random_scores(c->seed, step_idx, l, B, L_r, sc, st);
       launch_select(sc, B, L_r, c->k_sel,
                     sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
                     per_seq, sel_off, inv, n, L_p, st);
+      if (defer_v)
+        launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Vc, st);
     }
     S = 1;
     if (M_R > 0) {
@@ -499,7 +522,7 @@ int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache
                             static_cast<size_t>(rows) * d_kv * 8, st);
   if (S == 0) return DLLMC_ENOMEM;
   const RowKernelArgs ra{dtype, rows, 0, d, 0.f};
-  launch_v_finalize(ra, scratch, S, nullptr, rows, d_kv, v_cache, scores, st);
+  launch_v_finalize(ra, scratch, S, nullptr, rows, d_kv, v_cache, scores, 0, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;
 }

@@ -194,20 +194,24 @@ __global__ __launch_bounds__(kThreads) void k_embed_norm(const T* __restrict__ h
   }
 }
 
-// ---- V-verify epilogue: round V_new, cosine against the cached row, overwrite the cache --
+// ---- V-verify epilogue: round V_new, score it against the cached row (metric 0: cosine of
+// Eq. (cos_sim); 1: minus the Euclidean distance, the paper's L2 variant), overwrite the cache --
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict__ c_part, int S,
                                                          size_t slice_stride,
                                                          const int* __restrict__ rows, int d_kv,
                                                          int n, int L_p, T* __restrict__ v_cache,
-                                                         float* __restrict__ score) {
+                                                         float* __restrict__ score, int metric,
+                                                         T* __restrict__ v_stage) {
   __shared__ float red[kNW];
   const int i = blockIdx.x;
   const int row = rows ? rows[i] : i;
   T* vc = v_cache + static_cast<size_t>(row) * d_kv;
   const int pos = row % n;
   const bool scored = (score != nullptr) && (pos >= L_p);
-  float dot = 0.f, nn = 0.f, no = 0.f;
+  // selected-only update: response rows are parked in v_stage[i] until the selection is known
+  T* vdst = (v_stage != nullptr && pos >= L_p) ? v_stage + static_cast<size_t>(i) * d_kv : vc;
+  float dot = 0.f, nn = 0.f, no = 0.f;  // metric 1 (distance): dot holds sum (v - o)^2
   for (int c0 = 0; c0 < d_kv; c0 += kChunk(V)) {
     Vec<V> v[kRegVecs], o[kRegVecs];
     sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv, c0, d_kv, v);
@@ -222,14 +226,22 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
 #pragma unroll
         for (int e = 0; e < V; ++e) v[it].v[e] = roundf_to<T>(v[it].v[e]);
         if (scored) {
+          if (metric == 0) {
 #pragma unroll
-          for (int e = 0; e < V; ++e) {
-            dot += v[it].v[e] * o[it].v[e];
-            nn += v[it].v[e] * v[it].v[e];
-            no += o[it].v[e] * o[it].v[e];
+            for (int e = 0; e < V; ++e) {
+              dot += v[it].v[e] * o[it].v[e];
+              nn += v[it].v[e] * v[it].v[e];
+              no += o[it].v[e] * o[it].v[e];
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+              const float df = v[it].v[e] - o[it].v[e];
+              dot += df * df;
+            }
           }
         }
-        IO<T, V>::st(vc + c, v[it]);
+        IO<T, V>::st(vdst + c, v[it]);
       }
     }
   }
@@ -241,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
       const int seq = row / n;
       const int L_r = n - L_p;
       score[static_cast<size_t>(seq) * L_r + (pos - L_p)] =
-          dot / fmaxf(sqrtf(nn) * sqrtf(no), 1e-8f);
+          metric == 0 ? dot / fmaxf(sqrtf(nn) * sqrtf(no), 1e-8f) : -sqrtf(dot);
     }
   }
 }
@@ -403,6 +415,23 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
   }
 }
 
+// Selected-only V update: v_cache[row] = v_stage[carried index of row] for the recomputed
+// response rows (prompt rows were written directly).  Carried rows of a sequence are the
+// positions first .. n-1, carried_per_seq of them.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_scatter_v(const int* __restrict__ rows_R, int n,
+                                                        int L_p, int first, int carried_per_seq,
+                                                        int d_kv, const T* __restrict__ v_stage,
+                                                        T* __restrict__ v_cache) {
+  const int row = rows_R[blockIdx.x];
+  const int pos = row % n;
+  if (pos < L_p) return;  // uniform over the workgroup
+  const size_t i = static_cast<size_t>(row / n) * carried_per_seq + (pos - first);
+  const T* src = v_stage + i * d_kv;
+  T* dst = v_cache + static_cast<size_t>(row) * d_kv;
+  for (int c = threadIdx.x; c < d_kv; c += kThreads) dst[c] = src[c];
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_copy_prompt(const T* __restrict__ prompt_out, int n,
                                                           int L_p, int d,
@@ -467,17 +496,30 @@ void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int*
 }
 
 void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
-                       int d_kv, void* v_cache, float* score, hipStream_t st) {
+                       int d_kv, void* v_cache, float* score, int metric, void* v_stage,
+                       hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * d_kv;
-  const bool vec = vec_ok(d_kv, {c_part, v_cache});
+  const bool vec = vec_ok(d_kv, {c_part, v_cache, v_stage});
   if (a.dtype == 1) {
     DLLMC_ROW_LAUNCH(k_v_finalize, bf16_t, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
-                     P<bf16_t>(v_cache), score);
+                     P<bf16_t>(v_cache), score, metric, P<bf16_t>(v_stage));
   } else {
     DLLMC_ROW_LAUNCH(k_v_finalize, float, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
-                     P<float>(v_cache), score);
+                     P<float>(v_cache), score, metric, P<float>(v_stage));
   }
+}
+
+void launch_scatter_v(const RowKernelArgs& a, const int* rows_R, int M_R, int first,
+                      int carried_per_seq, int d_kv, const void* v_stage, void* v_cache,
+                      hipStream_t st) {
+  if (M_R <= 0) return;
+  if (a.dtype == 1)
+    hipLaunchKernelGGL(k_scatter_v<bf16_t>, dim3(M_R), dim3(kThreads), 0, st, rows_R, a.n, a.L_p, first,
+                       carried_per_seq, d_kv, P<bf16_t>(v_stage), P<bf16_t>(v_cache));
+  else
+    hipLaunchKernelGGL(k_scatter_v<float>, dim3(M_R), dim3(kThreads), 0, st, rows_R, a.n, a.L_p, first,
+                       carried_per_seq, d_kv, P<float>(v_stage), P<float>(v_cache));
 }
 
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,

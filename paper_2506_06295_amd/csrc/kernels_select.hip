@@ -116,7 +116,37 @@ __global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ s
   }
 }
 
+// MurmurHash3's 32-bit finalizer: a bijective avalanche mix
+__device__ __forceinline__ uint32_t fmix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x85EBCA6Bu;
+  x ^= x >> 13;
+  x *= 0xC2B2AE35u;
+  x ^= x >> 16;
+  return x;
+}
+
+// Scores of the random-selection baseline (paper Sec. 4.3): a counter-based uniform in [0, 1)
+// with 24 bits per (seed, step, layer, sequence, position): h = seed; for each of step, layer,
+// sequence, position: h = fmix32(h xor value); score = (h >> 8) * 2^-24.
+__global__ __launch_bounds__(kThreads) void k_random_scores(uint32_t seed, uint32_t step,
+                                                            uint32_t layer, int B, int L,
+                                                            float* __restrict__ out) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i >= B * L) return;
+  const uint32_t b = static_cast<uint32_t>(i / L), j = static_cast<uint32_t>(i % L);
+  const uint32_t h = fmix32(fmix32(fmix32(fmix32(seed ^ step) ^ layer) ^ b) ^ j);
+  out[i] = static_cast<float>(h >> 8) * 5.9604644775390625e-8f;  // 2^-24
+}
+
 }  // namespace
+
+void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, float* out,
+                          hipStream_t st) {
+  if (B * L <= 0) return;
+  hipLaunchKernelGGL(k_random_scores, dim3((B * L + kThreads - 1) / kThreads), dim3(kThreads), 0, st,
+                     seed, static_cast<uint32_t>(step), static_cast<uint32_t>(layer), B, L, out);
+}
 
 void launch_select(const float* scores, int B, int L, int k, int* sel_out, int sel_stride,
                    int* rows_out, int per_seq, int off, int* inv_out, int n, int L_p,

@@ -65,10 +65,13 @@ def make_pair(cfg: I.Config, weights: List[Dict[str, np.ndarray]], **over):
                                  n_kv_heads=cfg.H_kv, head_dim=cfg.d_h, d_ffn=cfg.m, batch=cfg.B,
                                  dtype=cfg.dtype, weights=dev_ws, L_p=cfg.L_p, L_r=cfg.L_r, rho=rho,
                                  K_p=K_p, K_r=K_r, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+    policy = {k: over[k] for k in ("metric", "selection", "v_update", "seed") if k in over}
+    if policy:
+        gpu.set_policy(**policy)
     ora = O.CachedDenoiser(oracle_model(cfg),
                            [{k: np.asarray(v, dtype=np.float64) for k, v in w.items()} for w in weights],
                            cfg.B, cfg.L_p, cfg.L_r, rho, K_p, K_r,
-                           storage="bf16" if cfg.dtype == "bf16" else "f64")
+                           storage="bf16" if cfg.dtype == "bf16" else "f64", **policy)
     return gpu, ora
 
 

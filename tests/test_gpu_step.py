@@ -115,6 +115,47 @@ def test_degenerate_shapes(cfg):
     gpu.close()
 
 
+POLICIES = [dict(metric="l2"), dict(selection="random", seed=1234), dict(v_update="selected"),
+            dict(metric="l2", v_update="selected"), dict(selection="random", seed=7, v_update="selected")]
+
+
+@pytest.mark.parametrize("policy", POLICIES, ids=lambda p: "-".join(f"{k}={v}" for k, v in p.items()))
+@pytest.mark.parametrize("cfg", [I.CONFIGS["toy"], MINI_LLADA], ids=lambda c: c.name)
+def test_selection_and_update_variants(cfg, policy):
+    """The variants the paper compares with its default: L2-distance score, random selection,
+    selected-only V update (and combinations), whole schedules against the oracle."""
+    gpu, ora, st = run_schedule(cfg, stress=True, **policy)
+    report(f"{cfg.name} {policy}", st)
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+    PU.compare_caches(cfg, gpu, ora, 1e-4 if cfg.dtype == "f32" else 2e-2)
+    if policy.get("selection") == "random":
+        # the scores are integers in disguise: both sides must agree bit for bit, and with
+        # them the selected sets
+        assert st.worst_score_dev == 0.0
+        assert st.followed == 0
+    gpu.close()
+
+
+def test_random_scores_match_the_counter_based_generator():
+    cfg = MINI_LLADA.replace(K_p=8, K_r=8, steps=4)
+    ws = I.all_weights(cfg)
+    gpu, _ = PU.make_pair(cfg, ws, selection="random", seed=0xC0FFEE)
+    sched = I.TokenSchedule(cfg)
+    for i in range(3):
+        gpu.step(PU.to_device(cfg, sched.hidden_in(i)), i)
+        if i == 0:
+            continue
+        got = gpu.read_scores()
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        for l in range(cfg.T):
+            for b in range(cfg.B):
+                want = O.random_scores(0xC0FFEE, i, l, b, cfg.L_r).astype(np.float32)
+                assert np.array_equal(got[l, b], want), (i, l, b)
+    gpu.close()
+
+
 @pytest.mark.parametrize("rho", [0.0, 0.05, 0.5, 1.0])
 def test_rho_sweep_bf16(rho):
     cfg = MINI_LLADA.replace(steps=4)
