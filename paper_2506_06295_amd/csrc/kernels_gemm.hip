@@ -320,12 +320,17 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int WM, int WN, int MI, int NJ>
+//   PAIR = 1 (fused gate/up + SwiGLU, single slice): the tile's weight rows are BN/2 rows of W0
+//        (gate) followed by the same BN/2 rows of W1 (up), so every lane ends up with the gate
+//        and the up sum of the same output element and stores bf16(silu(gate) * up) to U[M, N]
+//        (N = FFN width; the grid has N / (BN/2) column tiles).
+template <int WM, int WN, int MI, int NJ, int PAIR = 0>
 __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int lda,
                                               const int* __restrict__ rows, int M,
                                               const bf16_t* __restrict__ W0,
                                               const bf16_t* __restrict__ W1, int N0, int N, int K,
-                                              int k_per_slice, float* __restrict__ C) {
+                                              int k_per_slice, float* __restrict__ C,
+                                              bf16_t* __restrict__ U = nullptr) {
   constexpr int NWV = WM * WN;
   constexpr int BM = WM * MI * 16, BN = WN * NJ * 16;
   constexpr int LA = BM / 8 / NWV, LB = BN / 8 / NWV;  // load instructions per wavefront and step
@@ -337,7 +342,8 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   const int wm = wave / WN, wn = wave % WN;
   int col_tile, row_tile;
   xcd_tile_map(col_tile, row_tile);
-  const int m0 = row_tile * BM, n0 = col_tile * BN;
+  static_assert(!PAIR || NJ % 2 == 0, "gate and up column blocks come in pairs");
+  const int m0 = row_tile * BM, n0 = col_tile * (PAIR ? BN / 2 : BN);
   const int kbeg = blockIdx.z * k_per_slice;
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of kFatK
   const int nkt = klen / kFatK;
@@ -359,9 +365,15 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   for (int j = 0; j < LB; ++j) {
     const int r = 8 * (LB * wave + j) + lane / 8;
     const int chunk = (lane % 8) ^ (r % 8);
-    const int nn = n0 + r;  // < N: N % BN == 0
-    bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K : W1 + static_cast<size_t>(nn - N0) * K) +
-              kbeg + chunk * 8;
+    if (PAIR) {
+      // LDS weight rows [0, BN/2): gate rows n0 + r; [BN/2, BN): up rows n0 + r - BN/2
+      const int nn = n0 + (r % (BN / 2));  // < N: N % (BN/2) == 0
+      bsrc[j] = (r < BN / 2 ? W0 : W1) + static_cast<size_t>(nn) * K + kbeg + chunk * 8;
+    } else {
+      const int nn = n0 + r;  // < N: N % BN == 0
+      bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K
+                         : W1 + static_cast<size_t>(nn - N0) * K) + kbeg + chunk * 8;
+    }
   }
 #define DLLMC_LDS_ISSUE(stage, kt)                                                              \
   {                                                                                             \
@@ -402,7 +414,9 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
       }
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const int r = wn * (NJ * 16) + j * 16 + ln;
+        // PAIR: column blocks j < NJ/2 are gate, j >= NJ/2 the same columns of up
+        const int r = PAIR ? (j / (NJ / 2)) * (BN / 2) + wn * (NJ / 2 * 16) + (j % (NJ / 2)) * 16 + ln
+                           : wn * (NJ * 16) + j * 16 + ln;
         bf[j] = __builtin_bit_cast(bf16x8, lb[r * 8 + (c ^ (r % 8))]);
       }
 #pragma unroll
@@ -417,6 +431,23 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   }
 #undef DLLMC_LDS_ISSUE
 
+  if (PAIR) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = m0 + wm * (MI * 16) + i * 16 + lg * 4 + e;
+        if (m < M) {
+#pragma unroll
+          for (int j = 0; j < NJ / 2; ++j) {
+            const float g = acc[i][j][e], up = acc[i][j + NJ / 2][e];
+            U[static_cast<size_t>(m) * N + n0 + wn * (NJ / 2 * 16) + j * 16 + ln] =
+                f32_to_bf16(g / (1.0f + expf(-g)) * up);
+          }
+        }
+      }
+    return;
+  }
   float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -445,6 +476,23 @@ __global__ __launch_bounds__(256) void k_gemm_mid(const bf16_t* __restrict__ A, 
                                                   const bf16_t* __restrict__ W1, int N0, int N,
                                                   int K, int k_per_slice, float* __restrict__ C) {
   gemm_lds_body<2, 2, 4, 4>(A, lda, rows, M, W0, W1, N0, N, K, k_per_slice, C);
+}
+
+// fused gate/up + SwiGLU for many rows: N is the FFN width, grid.x = N / 128 (fat) or N / 64 (mid)
+__global__ __launch_bounds__(512) void k_gemm_fat_swiglu(const bf16_t* __restrict__ A, int lda,
+                                                         const int* __restrict__ rows, int M,
+                                                         const bf16_t* __restrict__ Wg,
+                                                         const bf16_t* __restrict__ Wu, int N, int K,
+                                                         bf16_t* __restrict__ U) {
+  gemm_lds_body<2, 4, 8, 4, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
+}
+
+__global__ __launch_bounds__(256) void k_gemm_mid_swiglu(const bf16_t* __restrict__ A, int lda,
+                                                         const int* __restrict__ rows, int M,
+                                                         const bf16_t* __restrict__ Wg,
+                                                         const bf16_t* __restrict__ Wu, int N, int K,
+                                                         bf16_t* __restrict__ U) {
+  gemm_lds_body<2, 2, 4, 4, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
 }
 
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
@@ -638,6 +686,24 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   // two wavefront groups over the two halves of K when the halves are whole phases
   const int KH = (g_tune.nw_dual >= 100 && K % (2 * KC) == 0) ? 2 : 1;
   const int BN = 16 * NW / KH;
+  if (M >= g_tune.tile_min_m && stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && K % kFatK == 0) {
+    // many rows: the LDS-direct tile kernels with paired gate/up column blocks, one slice
+    const bool fat = M >= g_tune.fat_min_m && m % (kFatN / 2) == 0;
+    if (fat || m % (kMidN / 2) == 0) {
+      t_last_stream = false;
+      const bf16_t* a = static_cast<const bf16_t*>(A);
+      const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
+      const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
+      bf16_t* uo = static_cast<bf16_t*>(u);
+      if (fat)
+        hipLaunchKernelGGL(k_gemm_fat_swiglu, dim3(m / (kFatN / 2), (M + kFatM - 1) / kFatM, 1),
+                           dim3(512), 0, st, a, lda, rows, M, w0, w1, m, K, uo);
+      else
+        hipLaunchKernelGGL(k_gemm_mid_swiglu, dim3(m / (kMidN / 2), (M + kMidM - 1) / kMidM, 1),
+                           dim3(256), 0, st, a, lda, rows, M, w0, w1, m, K, uo);
+      return true;
+    }
+  }
   if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % BN == 0) || M > 128) return false;
   const dim3 grid(m / BN, (M + 63) / 64, 1);
   t_last_stream = true;

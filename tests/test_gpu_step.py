@@ -115,6 +115,23 @@ def test_degenerate_shapes(cfg):
     gpu.close()
 
 
+@pytest.mark.parametrize("fat_min_m", [1024, 64], ids=["mid_tiles", "fat_tiles"])
+@pytest.mark.parametrize("cfg", [MINI_LLADA, MINI_DREAM], ids=lambda c: c.name)
+def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
+    """Refresh steps (hundreds of rows) run gate/up + SwiGLU fused inside the LDS-direct tile
+    kernels (128 x 128 by default, 256 x 256 when forced); MINI_DREAM's FFN width (2432 = 38 x 64)
+    fits the 128-wide pairing only, so its forced case falls back to the narrower kernel."""
+    binding.set_gemm_tuning(fat_min_m=fat_min_m)
+    try:
+        gpu, ora, st = run_schedule(cfg.replace(steps=4), stress=True, K_r=1)   # every step refreshes the response
+        assert st.failed == 0, st.failures
+        assert st.worst_rel <= 2e-2
+        PU.compare_caches(cfg, gpu, ora, 2e-2)
+        gpu.close()
+    finally:
+        binding.set_gemm_tuning(fat_min_m=1024)
+
+
 POLICIES = [dict(metric="l2"), dict(selection="random", seed=1234), dict(v_update="selected"),
             dict(metric="l2", v_update="selected"), dict(selection="random", seed=7, v_update="selected")]
 
