@@ -37,7 +37,9 @@ def check_select(scores, k):
 
 @pytest.mark.parametrize("B,L,k", [(1, 32, 8), (1, 256, 64), (1, 512, 51), (16, 256, 12),
                                    (16, 256, 128), (16, 256, 256), (3, 1000, 333), (2, 5000, 1234),
-                                   (1, 1, 1), (1, 7, 0), (4, 257, 256)])
+                                   (1, 1, 1), (1, 7, 0), (4, 257, 256),
+                                   (2, 8192, 2048),     # the longest sequence whose keys stay in LDS
+                                   (2, 8193, 100), (1, 20000, 5000)])  # beyond it: keys re-read from memory
 def test_select_random_scores(B, L, k):
     r = np.random.default_rng(L * 31 + k)
     check_select(r.uniform(-1, 1, size=(B, L)).astype(np.float32), k)
