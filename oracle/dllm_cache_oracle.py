@@ -275,18 +275,24 @@ class CachedDenoiser:
     def __init__(self, model: Model, weights: Sequence[Dict[str, np.ndarray]], B: int,
                  L_p: int, L_r: int, rho: float, K_p: int, K_r: int,
                  storage: str = "f64", dtype=np.float64, metric: str = "cosine",
-                 selection: str = "verify", v_update: str = "all", seed: int = 0):
-        """metric / selection / v_update pick the variants the paper compares with its default
-        (cosine V-verify, whole-V overwrite): metric "l2" (appendix "Impact of Similarity
-        Metric"), selection "random" (Sec. 4.3), v_update "selected" (appendix "Design Choice
-        Between Full V-Cache Overwrite and Selective Update": only the selected rows' Values
-        are written back, the others keep the cached ones)."""
+                 selection: str = "verify", v_update: str = "all", seed: int = 0,
+                 source: str = "v"):
+        """metric / selection / v_update / source pick the variants the paper compares with its
+        default (cosine V-verify, whole-V overwrite): metric "l2" (appendix "Impact of
+        Similarity Metric"), selection "random" (Sec. 4.3), v_update "selected" (appendix
+        "Design Choice Between Full V-Cache Overwrite and Selective Update": only the selected
+        rows of the verified tensor are written back, the others keep the cached ones), source
+        "k" (K-verify, Sec. 4.3: the roles of K and V are exchanged: the Key rows, after RoPE,
+        of all response rows are computed, scored against the cached Keys and written back,
+        and the Values are recomputed and scattered for the selected rows only; the paper names
+        the strategy without spelling it out, this is the mirror image of its V-verify)."""
         if not (0.0 <= rho <= 1.0) or K_p < 1 or K_r < 1:
             raise ValueError("need 0 <= rho <= 1 and K_p, K_r >= 1")
         if metric not in ("cosine", "l2") or selection not in ("verify", "random") or \
-                v_update not in ("all", "selected"):
+                v_update not in ("all", "selected") or source not in ("v", "k"):
             raise ValueError("unknown policy")
         self.metric, self.selection, self.v_update, self.seed = metric, selection, v_update, seed
+        self.source = source
         self.model, self.weights = model, weights
         self.B, self.L_p, self.L_r, self.n = B, L_p, L_r, L_p + L_r
         self.rho, self.K_p, self.K_r = rho, K_p, K_r
@@ -338,8 +344,14 @@ class CachedDenoiser:
             for l in range(mo.T):
                 W = _as(self.weights[l], dt)
                 h = st(rmsnorm(x, W["attn_norm_g"], mo.rms_eps))
-                # V-verify: current Value rows of every carried row
-                V_new = st(h @ W["wv"].T)
+                # the verified tensor (V by default, K after RoPE for K-verify) of every carried row
+                k_src = self.source == "k"
+                if k_src:
+                    T_new = st(rope(h @ W["wk"].T, C, mo.d_h, mo.rope_theta))
+                    cache = self.K[l]
+                else:
+                    T_new = st(h @ W["wv"].T)
+                    cache = self.V[l]
                 self.macs += h.shape[0] * mo.d * mo.d_kv
                 if Rf:
                     S = np.arange(L_r)
@@ -347,9 +359,9 @@ class CachedDenoiser:
                     if self.selection == "random":
                         s = random_scores(self.seed, i, l, b, L_r)
                     elif self.metric == "l2":
-                        s = l2_scores(V_new[resp_in_C], self.V[l][b, L_p:])
+                        s = l2_scores(T_new[resp_in_C], cache[b, L_p:])
                     else:
-                        s = cosine_scores(V_new[resp_in_C], self.V[l][b, L_p:])
+                        s = cosine_scores(T_new[resp_in_C], cache[b, L_p:])
                     S = bottom_k(s, self.k_sel)
                     rep.scores[l][b] = s
                     rep.gaps[l][b] = boundary_gap(s, self.k_sel)
@@ -360,23 +372,23 @@ class CachedDenoiser:
                     if forced_sel is not None:
                         S = np.sort(np.asarray(forced_sel[l][b], dtype=np.int64))
                 rep.selected[l][b] = S
-                if self.v_update == "all" or Rf:
-                    # the whole response V (and the prompt V on a prompt refresh) is overwritten
-                    self.V[l][b, C] = V_new
-                else:
-                    # variant: only the selected rows (and a refreshed prompt) take their new Values
-                    upd = np.concatenate([np.arange(L_p) if P else np.zeros(0, dtype=np.int64),
-                                          L_p + S]).astype(np.int64)
-                    self.V[l][b, upd] = V_new[upd - off]
-                # rows whose K / AttnOut / FFNOut are recomputed
+                # rows whose other projections, AttnOut and FFNOut are recomputed
                 R = np.concatenate([np.arange(L_p) if P else np.zeros(0, dtype=np.int64),
                                     L_p + S]).astype(np.int64)
+                if self.v_update == "all" or Rf:
+                    # the whole verified tensor of the response (and of a refreshed prompt) is overwritten
+                    cache[b, C] = T_new
+                else:
+                    # variant: only the selected rows (and a refreshed prompt) take their new rows
+                    cache[b, R] = T_new[R - off]
                 if R.size:
                     hR = h[R - off]
                     Q_R = st(rope(hR @ W["wq"].T, R, mo.d_h, mo.rope_theta))
-                    K_R = st(rope(hR @ W["wk"].T, R, mo.d_h, mo.rope_theta))
+                    if k_src:
+                        self.V[l][b, R] = st(hR @ W["wv"].T)
+                    else:
+                        self.K[l][b, R] = st(rope(hR @ W["wk"].T, R, mo.d_h, mo.rope_theta))
                     self.macs += R.size * mo.d * (mo.d_q + mo.d_kv)
-                    self.K[l][b, R] = K_R
                     # queries in R attend to all n cached keys/values (updated above)
                     A_R = st(attention(Q_R, self.K[l][b], self.V[l][b], mo.H_q, mo.H_kv, mo.d_h))
                     self.macs += 2 * R.size * n * mo.d_q

@@ -117,3 +117,47 @@ def test_unknown_policy_is_rejected():
     cfg = small_cfg()
     with pytest.raises(ValueError):
         make(cfg, I.all_weights(cfg), metric="manhattan")
+
+
+def test_k_verify_is_the_mirror_image_of_v_verify():
+    cfg = small_cfg(K_p=8, K_r=8, L_r=16, rho=0.25)
+    ws = I.all_weights(cfg)
+    kv, vv = make(cfg, ws, source="k"), make(cfg, ws)
+    sched = I.TokenSchedule(cfg, stress=True)
+    o_k, _ = kv.step(sched.hidden_in(0).astype(np.float64), 0)
+    o_v, _ = vv.step(sched.hidden_in(0).astype(np.float64), 0)
+    assert np.array_equal(o_k, o_v)                       # refresh steps do not depend on the variant
+    k_before = [k.copy() for k in kv.K]
+    v_before = [v.copy() for v in kv.V]
+    _, rep = kv.step(sched.hidden_in(1).astype(np.float64), 1)
+    # layer 0: the scores are the cosines between the Keys now in the cache and those before
+    s0 = O.cosine_scores(kv.K[0][0, cfg.L_p:], k_before[0][0, cfg.L_p:])
+    assert np.allclose(rep.scores[0][0], s0, rtol=1e-12)
+    assert rep.selected[0][0].tolist() == O.bottom_k(s0, kv.k_sel).tolist()
+    for l in range(cfg.T):
+        S = rep.selected[l][0]
+        rest = np.setdiff1d(np.arange(cfg.L_r), S)
+        # every response Key is rewritten, Values only for the selected rows
+        assert not np.any(np.all(kv.K[l][0, cfg.L_p:] == k_before[l][0, cfg.L_p:], axis=1))
+        assert np.array_equal(kv.V[l][0, cfg.L_p + rest], v_before[l][0, cfg.L_p + rest])
+        assert not np.array_equal(kv.V[l][0, cfg.L_p + S], v_before[l][0, cfg.L_p + S])
+        # the prompt side is untouched on a step that does not refresh it
+        assert np.array_equal(kv.K[l][0, :cfg.L_p], k_before[l][0, :cfg.L_p])
+    # the rotation does not change a row's norm, so the cached Keys have the norms of the plain projection
+    mo = kv.model
+    x = sched.hidden_in(1).astype(np.float64)[0, cfg.L_p:]
+    h = O.rmsnorm(x, np.asarray(ws[0]["attn_norm_g"], dtype=np.float64), mo.rms_eps)
+    plain = h @ np.asarray(ws[0]["wk"], dtype=np.float64).T
+    assert np.allclose(np.linalg.norm(kv.K[0][0, cfg.L_p:], axis=1), np.linalg.norm(plain, axis=1), rtol=1e-12)
+
+
+def test_k_verify_with_every_row_selected_equals_the_default():
+    cfg = small_cfg(K_p=3, K_r=4, L_r=16, rho=1.0)
+    ws = I.all_weights(cfg)
+    a, b = make(cfg, ws, source="k"), make(cfg, ws)
+    sched = I.TokenSchedule(cfg, stress=True)
+    for i in range(6):
+        oa, _ = a.step(sched.hidden_in(i).astype(np.float64), i)
+        ob, _ = b.step(sched.hidden_in(i).astype(np.float64), i)
+        assert np.allclose(oa, ob, rtol=1e-12, atol=1e-12)
+    assert a.macs == b.macs
