@@ -89,17 +89,21 @@ int32_t dllmc_num_selected(const dllmc_ctx* ctx);
 
 /* Variants the paper compares with its default (cosine V-verify with whole-V overwrite);
  * take effect at the next dllmc_step, normally set before step 0.
+ *   source     0: V-verify; 1: K-verify (Sec. 4.3), taken as its mirror image: on an adaptive step
+ *              the Key rows (after RoPE) of all response rows are computed, scored against the
+ *              cached Keys and written back, the Values are recomputed and scattered for the
+ *              selected rows only; dllmc_read_scores then returns the Key scores
  *   metric     0: cosine of Eq. (cos_sim); 1: minus the Euclidean distance between the current
  *              and the cached Value row (appendix "Impact of Similarity Metric")
  *   selection  0: the floor(rho*L_r) lowest scores; 1: random rows (Sec. 4.3): the scores are
  *              24-bit uniforms h >> 8 scaled by 2^-24, h = seed, then for each of step_idx,
  *              layer, sequence, position: h = fmix32(h xor value), fmix32 being the 32-bit
  *              finalizer of MurmurHash3; dllmc_read_scores returns them
- *   v_update   0: the whole response V is overwritten on an adaptive step; 1: only the selected
- *              rows' Values are written back (appendix "Design Choice Between Full V-Cache
- *              Overwrite and Selective Update") */
-int dllmc_set_policy(dllmc_ctx* ctx, int32_t metric, int32_t selection, int32_t v_update,
-                     uint32_t seed);
+ *   v_update   0: the whole verified tensor of the response is overwritten on an adaptive step;
+ *              1: only the selected rows are written back (appendix "Design Choice Between Full
+ *              V-Cache Overwrite and Selective Update") */
+int dllmc_set_policy(dllmc_ctx* ctx, int32_t source, int32_t metric, int32_t selection,
+                     int32_t v_update, uint32_t seed);
 
 /* One denoising step (Sec. 3.2 "Iterative Steps").
  *   hidden_in  device [B, L_p+L_r, d], model dtype: embedded tokens of this step.

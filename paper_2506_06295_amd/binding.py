@@ -102,7 +102,7 @@ def lib() -> C.CDLL:
                                          C.c_void_p, C.c_void_p, C.c_void_p]
         L.dllmc_op_attention_scratch_bytes.restype = C.c_size_t
         L.dllmc_set_policy.restype = C.c_int
-        L.dllmc_set_policy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
+        L.dllmc_set_policy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_uint32]
         L.dllmc_gen_workspace_bytes.restype = C.c_size_t
         L.dllmc_gen_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(dllmc_gen_config)]
         L.dllmc_gen_create.restype = C.c_int
@@ -204,9 +204,9 @@ class CachedDenoiser:
         return hidden_out, n_sel.value
 
     def set_policy(self, metric: str = "cosine", selection: str = "verify", v_update: str = "all",
-                   seed: int = 0) -> None:
+                   seed: int = 0, source: str = "v") -> None:
         """Variants of the paper's ablations; see dllmc_set_policy."""
-        _check(lib().dllmc_set_policy(self._h, {"cosine": 0, "l2": 1}[metric],
+        _check(lib().dllmc_set_policy(self._h, {"v": 0, "k": 1}[source], {"cosine": 0, "l2": 1}[metric],
                                       {"verify": 0, "random": 1}[selection],
                                       {"all": 0, "selected": 1}[v_update], seed & 0xFFFFFFFF),
                "dllmc_set_policy")

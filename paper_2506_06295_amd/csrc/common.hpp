@@ -123,9 +123,16 @@ void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, floa
 // Q/K finalize: for i < M: row = rows[i], pos = row % n; c = sum_s c_part[s][i][0..d_q+d_kv);
 // q_out[i] = T(rope(c[0..d_q))), k_cache[row] = T(rope(c[d_q..))).  rope_tab[pos][t] =
 // (cos, sin) of pos * theta^(-2t/d_h).
+// rope_second = false: the second matrix' columns are stored unrotated (K-verify: they are the
+// Values of the selected rows and k_cache is the V cache).
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                         int d_q, int d_kv, int d_h, const float2* rope_tab, void* q_out,
-                        void* k_cache, hipStream_t st);
+                        void* k_cache, bool rope_second, hipStream_t st);
+// K finalize (K-verify): like launch_v_finalize on the Key projection, with RoPE at the row's
+// position before rounding, scoring and the cache write.
+void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
+                       int d_kv, int d_h, const float2* rope_tab, void* k_cache, float* score,
+                       int metric, void* k_stage, hipStream_t st);
 
 // Output-projection finalize over the carried rows: for i < Mc: row = carried[i]; ci = inv[row];
 // if ci >= 0: attn_cache[row] = T(sum_s c_part[s][ci][:]) (c_part slices hold M_R rows);

@@ -106,6 +106,7 @@ struct dllmc_ctx {
   bool have_scores;
   // variants of the paper's ablations (dllmc_set_policy); defaults are the paper's method
   int metric = 0;          // 0 cosine, 1 minus L2 distance
+  bool source_k = false;   // K-verify: Keys are scored and overwritten, Values follow the selection
   bool random_sel = false;
   bool v_selected_only = false;
   uint32_t seed = 0;
@@ -226,10 +227,12 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
 
 int32_t dllmc_num_selected(const dllmc_ctx* ctx) { return ctx ? ctx->k_sel : DLLMC_EINVAL; }
 
-int dllmc_set_policy(dllmc_ctx* c, int32_t metric, int32_t selection, int32_t v_update,
-                     uint32_t seed) {
-  if (!c || metric < 0 || metric > 1 || selection < 0 || selection > 1 || v_update < 0 || v_update > 1)
+int dllmc_set_policy(dllmc_ctx* c, int32_t source, int32_t metric, int32_t selection,
+                     int32_t v_update, uint32_t seed) {
+  if (!c || source < 0 || source > 1 || metric < 0 || metric > 1 || selection < 0 || selection > 1 ||
+      v_update < 0 || v_update > 1)
     return DLLMC_EINVAL;
+  c->source_k = source == 1;
   c->metric = metric;
   c->random_sel = selection == 1;
   c->v_selected_only = v_update == 1;
@@ -309,21 +312,30 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     const dllmc_layer_weights& w = c->layers[l];
     void* Kc = c->cache(0, l);
     void* Vc = c->cache(1, l);
-    // V-verify: V for every carried row, score against the cache, overwrite the cache
+    // Verify: the verified projection (V; K for the K-verify variant) for every carried row,
+    // scored against the cache, cache overwritten.  Refresh steps always go V first.
+    const bool ksrc = c->source_k && !Rf;
+    void* Tc = ksrc ? Kc : Vc;   // cache of the verified tensor
     int S;
     {
       Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
-      S = launch_gemm(dt, h, d, carried, Mc, w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap, st);
+      S = launch_gemm(dt, h, d, carried, Mc, ksrc ? w.wk : w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap,
+                      st);
       if (S == 0) return DLLMC_ENOMEM;
     }
     float* sc = scores + static_cast<size_t>(l) * B * L_r;
-    // selected-only V update: the response rows' new Values wait in the attention output
-    // buffer (free until this layer's attention) for the selection
+    // selected-only update: the response rows' new rows wait in the attention output buffer
+    // (free until this layer's attention) for the selection
     const bool defer_v = c->v_selected_only && !Rf;
     {
       Timed t(c, DLLMC_KC_ROW, Mc * d_kv * (4.0 + 2.0 * esz), 0);
-      launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Vc, (Rf || c->random_sel) ? nullptr : sc,
-                        c->metric, defer_v ? abuf : nullptr, st);
+      float* sc_out = (Rf || c->random_sel) ? nullptr : sc;
+      if (ksrc)
+        launch_k_finalize(ra, cws, S, carried, Mc, d_kv, d_h, rope_tab, Tc, sc_out, c->metric,
+                          defer_v ? abuf : nullptr, st);
+      else
+        launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Tc, sc_out, c->metric,
+                          defer_v ? abuf : nullptr, st);
     }
     if (!Rf) {
       Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + c->k_sel * 8.0 + L_r * 4.0), 0);
@@ -332,18 +344,21 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
                     sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
                     per_seq, sel_off, inv, n, L_p, st);
       if (defer_v)
-        launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Vc, st);
+        launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Tc, st);
     }
     S = 1;
     if (M_R > 0) {
       {
+        // Q and the other projection (K; V for K-verify) of the recomputed rows in one launch
         Timed t(c, DLLMC_KC_GEMM_QK, gemm_bytes(M_R, d_q + d_kv, d), gemm_flops(M_R, d_q + d_kv, d));
-        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, w.wk, d_q, d_q + d_kv, d, cws, cws_cap, st);
+        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, ksrc ? w.wv : w.wk, d_q, d_q + d_kv, d, cws,
+                        cws_cap, st);
         if (S == 0) return DLLMC_ENOMEM;
       }
       {
         Timed t(c, DLLMC_KC_ROW, M_R * (d_q + d_kv) * (4.0 + esz), 0);
-        launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, Kc, st);
+        launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, ksrc ? Vc : Kc,
+                           !ksrc, st);
       }
       {
         // queries in and out once, every sequence's K and V once per group of query heads

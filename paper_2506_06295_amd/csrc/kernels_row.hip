@@ -266,7 +266,8 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
                                                     const int* __restrict__ rows, int n, int d_q,
                                                     int d_kv, int d_h,
                                                     const float2* __restrict__ rope_tab,
-                                                    T* __restrict__ q_out, T* __restrict__ k_cache) {
+                                                    T* __restrict__ q_out, T* __restrict__ k_cache,
+                                                    int rope_second) {
   const int i = blockIdx.x, head = blockIdx.y;
   const int row = rows[i];
   const int pos = row % n;
@@ -280,9 +281,63 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
     const size_t off = static_cast<size_t>(i) * width + c0 + t;
     float2 ab;
     DLLMC_SWITCH_SLICES(S, NS, ab = sum_slices_pair<NS>(c_part, slice_stride, off, off + half))
-    const float2 cs = tab[t];
+    // the second matrix is W_k (rotated) or, for K-verify, W_v (stored as it is)
+    const float2 cs = (c0 < d_q || rope_second) ? tab[t] : make_float2(1.f, 0.f);
     stf(dst + t, ab.x * cs.x - ab.y * cs.y);
     stf(dst + t + half, ab.y * cs.x + ab.x * cs.y);
+  }
+}
+
+// ---- K-verify epilogue: RoPE at the row's position, round, score against the cached Key row
+// (metric as in k_v_finalize), overwrite the cache (or park response rows in k_stage) -------
+// One workgroup per row; a thread handles the rotation pairs (t, t + d_h/2) p = tid, tid+256, ...
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_k_finalize(const float* __restrict__ c_part, int S,
+                                                         size_t slice_stride,
+                                                         const int* __restrict__ rows, int d_kv,
+                                                         int d_h, int n, int L_p,
+                                                         const float2* __restrict__ rope_tab,
+                                                         T* __restrict__ k_cache,
+                                                         float* __restrict__ score, int metric,
+                                                         T* __restrict__ k_stage) {
+  __shared__ float red[kNW];
+  const int i = blockIdx.x;
+  const int row = rows ? rows[i] : i;
+  const int pos = row % n;
+  const int half = d_h / 2;
+  T* kc = k_cache + static_cast<size_t>(row) * d_kv;
+  T* kdst = (k_stage != nullptr && pos >= L_p) ? k_stage + static_cast<size_t>(i) * d_kv : kc;
+  const bool scored = (score != nullptr) && (pos >= L_p);
+  const float2* tab = rope_tab + static_cast<size_t>(pos) * half;
+  float dot = 0.f, nn = 0.f, no = 0.f;
+  for (int p = threadIdx.x; p < d_kv / 2; p += kThreads) {
+    const int t = p % half, c = (p / half) * d_h + t;  // columns c and c + half of the row
+    const size_t off = static_cast<size_t>(i) * d_kv + c;
+    float2 ab;
+    DLLMC_SWITCH_SLICES(S, NS, ab = sum_slices_pair<NS>(c_part, slice_stride, off, off + half))
+    const float2 cs = tab[t];
+    const float v0 = roundf_to<T>(ab.x * cs.x - ab.y * cs.y);
+    const float v1 = roundf_to<T>(ab.y * cs.x + ab.x * cs.y);
+    if (scored) {
+      const float o0 = ldf(kc + c), o1 = ldf(kc + c + half);
+      if (metric == 0) {
+        dot += v0 * o0 + v1 * o1;
+        nn += v0 * v0 + v1 * v1;
+        no += o0 * o0 + o1 * o1;
+      } else {
+        dot += (v0 - o0) * (v0 - o0) + (v1 - o1) * (v1 - o1);
+      }
+    }
+    stf(kdst + c, v0);
+    stf(kdst + c + half, v1);
+  }
+  if (scored) {
+    dot = block_sum<kNW>(dot, red);
+    nn = block_sum<kNW>(nn, red);
+    no = block_sum<kNW>(no, red);
+    if (threadIdx.x == 0)
+      score[static_cast<size_t>(row / n) * (n - L_p) + (pos - L_p)] =
+          metric == 0 ? dot / fmaxf(sqrtf(nn) * sqrtf(no), 1e-8f) : -sqrtf(dot);
   }
 }
 
@@ -524,16 +579,33 @@ void launch_scatter_v(const RowKernelArgs& a, const int* rows_R, int M_R, int fi
 
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                         int d_q, int d_kv, int d_h, const float2* rope_tab, void* q_out,
-                        void* k_cache, hipStream_t st) {
+                        void* k_cache, bool rope_second, hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * (d_q + d_kv);
   const dim3 grid(M, (d_q + d_kv) / d_h);
   if (a.dtype == 1)
     hipLaunchKernelGGL(k_qk_finalize<bf16_t>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
-                       d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache));
+                       d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache),
+                       rope_second ? 1 : 0);
   else
     hipLaunchKernelGGL(k_qk_finalize<float>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
-                       d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache));
+                       d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache),
+                       rope_second ? 1 : 0);
+}
+
+void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
+                       int d_kv, int d_h, const float2* rope_tab, void* k_cache, float* score,
+                       int metric, void* k_stage, hipStream_t st) {
+  if (M <= 0) return;
+  const size_t stride = static_cast<size_t>(M) * d_kv;
+  if (a.dtype == 1)
+    hipLaunchKernelGGL(k_k_finalize<bf16_t>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
+                       d_kv, d_h, a.n, a.L_p, rope_tab, P<bf16_t>(k_cache), score, metric,
+                       P<bf16_t>(k_stage));
+  else
+    hipLaunchKernelGGL(k_k_finalize<float>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
+                       d_kv, d_h, a.n, a.L_p, rope_tab, P<float>(k_cache), score, metric,
+                       P<float>(k_stage));
 }
 
 void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,

@@ -65,7 +65,7 @@ def make_pair(cfg: I.Config, weights: List[Dict[str, np.ndarray]], **over):
                                  n_kv_heads=cfg.H_kv, head_dim=cfg.d_h, d_ffn=cfg.m, batch=cfg.B,
                                  dtype=cfg.dtype, weights=dev_ws, L_p=cfg.L_p, L_r=cfg.L_r, rho=rho,
                                  K_p=K_p, K_r=K_r, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
-    policy = {k: over[k] for k in ("metric", "selection", "v_update", "seed") if k in over}
+    policy = {k: over[k] for k in ("metric", "selection", "v_update", "seed", "source") if k in over}
     if policy:
         gpu.set_policy(**policy)
     ora = O.CachedDenoiser(oracle_model(cfg),

@@ -133,11 +133,12 @@ def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
 
 
 POLICIES = [dict(metric="l2"), dict(selection="random", seed=1234), dict(v_update="selected"),
-            dict(metric="l2", v_update="selected"), dict(selection="random", seed=7, v_update="selected")]
+            dict(metric="l2", v_update="selected"), dict(selection="random", seed=7, v_update="selected"),
+            dict(source="k"), dict(source="k", metric="l2", v_update="selected")]
 
 
 @pytest.mark.parametrize("policy", POLICIES, ids=lambda p: "-".join(f"{k}={v}" for k, v in p.items()))
-@pytest.mark.parametrize("cfg", [I.CONFIGS["toy"], MINI_LLADA], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [I.CONFIGS["toy"], MINI_LLADA, MINI_DREAM], ids=lambda c: c.name)
 def test_selection_and_update_variants(cfg, policy):
     """The variants the paper compares with its default: L2-distance score, random selection,
     selected-only V update (and combinations), whole schedules against the oracle."""
