@@ -80,6 +80,10 @@ constexpr int kMaxKeySplit = 8;
 // tile is transposed through LDS once per workgroup.  K fragments and the next V tile are
 // fetched one block ahead.  With KS == 1 the normalised output is written; otherwise the
 // un-normalised partial (O, m, l) of this key range goes to `part` for k_attn_merge.
+// PRELOAD: every key range is at most kPreload blocks long (the launcher guarantees it) and is
+// fetched whole before its first use; the other instantiation walks its range block by block
+// and, without the preloaded fragments, keeps its accumulators in ordinary registers.
+template <bool PRELOAD>
 __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q, int Mq,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
@@ -214,7 +218,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
   };
 
   const int nb = blk1 - blk0;
-  if (nb > 0 && nb <= kPreload) {
+  if (PRELOAD && nb > 0) {
     // Short key range (split keys of an adaptive step): every K fragment and V tile of the
     // range is requested before the first one is used, so the range costs one trip to memory
     // instead of one per block.
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
 #pragma unroll
     for (int j = 0; j < kPreload; ++j)
       if (j < nb) process(kall[j], Vt[j], (blk0 + j) * 32);
-  } else if (nb > 0) {
+  } else if (!PRELOAD && nb > 0) {
     uint4 vraw[2];
     bf16x8 kf[2][4];
     load_v(blk0, vraw);
@@ -353,8 +357,12 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
       if (KS > kMaxKeySplit) KS = kMaxKeySplit;
       if (KS > nblk / 2) KS = nblk / 2 > 0 ? nblk / 2 : 1;  // at least two blocks per range
     }
-    hipLaunchKernelGGL(k_attn_mfma, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
-                       H_kv, KS, oo, scratch);
+    if ((nblk + KS - 1) / KS <= kPreload)
+      hipLaunchKernelGGL(k_attn_mfma<true>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
+                         H_q, H_kv, KS, oo, scratch);
+    else
+      hipLaunchKernelGGL(k_attn_mfma<false>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
+                         H_q, H_kv, KS, oo, scratch);
     if (KS > 1)
       hipLaunchKernelGGL(k_attn_merge, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, H_q, oo);
     return;
