@@ -91,6 +91,7 @@ def main():
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for HBM counters)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the achievable-peak probes")
     ap.add_argument("--no-closed-loop", action="store_true",
                     help="skip the closed-loop generation leg (embedding, head, remasking)")
     ap.add_argument("--tune", default="", help="GEMM tuning knobs, e.g. nw=8,nw_dual=4,force_s=0,target_wg=256")
@@ -260,6 +261,47 @@ def main():
                 "TFLOPs": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 else 0.0}
             for k, v in stats.items()}
         result["kernel_time_ms_per_step"] = total_ms / K
+
+    # what this GPU delivers for the plainest kernels (1 GiB copy, 1 GiB read, MFMA loop from
+    # registers): the measured ceilings beside the published peaks
+    if not args.no_probes:
+        n_probe = 1 << 30
+        src = torch.empty(n_probe, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+
+        def timed(fn, reps=10):
+            for _ in range(2):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ts = []
+            for _ in range(reps):
+                a.record()
+                fn()
+                b.record()
+                b.synchronize()
+                ts.append(a.elapsed_time(b) * 1e-3)
+            return float(np.median(ts))
+
+        t_copy = timed(lambda: binding.probe_copy(src, dst))
+        t_read = timed(lambda: binding.probe_read(src, sink))
+        fl = [0.0]
+
+        def mfma():
+            fl[0] = binding.probe_mfma(4096, sink)
+        t_mfma = timed(mfma)
+        copy_gbs, read_gbs, mfma_tf = 2 * n_probe / t_copy / 1e9, n_probe / t_read / 1e9, fl[0] / t_mfma / 1e12
+        result["achievable"] = {
+            "copy_GBps": copy_gbs, "read_GBps": read_gbs, "mfma_bf16_TFLOPs": mfma_tf,
+            "note": "1 GiB plain copy (bytes in + bytes out), 1 GiB plain read, back-to-back "
+                    "16x16x32 bf16 MFMAs from registers; median of 10 launches",
+        }
+        rf = result.get("roofline")
+        if rf:
+            ceil = read_gbs if rf["bound"] == "hbm" else mfma_tf
+            rf["frac_of_measured_ceiling"] = rf["achieved"] / ceil if ceil > 0 else None
+            rf["measured_ceiling"] = ceil
+        del src, dst
 
     # the uncached forward on the same GPU: rho = 1, K_p = K_r = 1
     if not args.no_uncached:

@@ -270,6 +270,22 @@ int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, cons
                        const void* v_cache, int32_t n, int32_t H_q, int32_t H_kv, int32_t d_h,
                        void* out, float* scratch, void* hip_stream);
 
+/* ---- achievable-peak probes (measurement aids, not steps of the method) ----
+ * What this GPU delivers for the plainest kernels of each kind, so that a roofline fraction
+ * can be quoted against a measured ceiling beside the published one.  All three only enqueue
+ * one kernel on hip_stream; the caller times them.
+ *   dllmc_probe_copy  dst[0..bytes) = src[0..bytes); device pointers, 16-byte aligned, bytes a
+ *                     multiple of 16; moves bytes in and bytes out.
+ *   dllmc_probe_read  reads src[0..bytes) once and writes nothing (sink: device, 4 bytes, is
+ *                     only there to keep the loads alive).
+ *   dllmc_probe_mfma  every wavefront of a grid that fills the chip issues iters * 8 independent
+ *                     16x16x32 bf16 MFMAs from registers; *flops_out (host, may be NULL) = the
+ *                     flops of the launch; sink: device float32 [256], 16-byte aligned,
+ *                     overwritten. */
+int dllmc_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+int dllmc_probe_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+int dllmc_probe_mfma(int32_t iters, float* sink, double* flops_out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,6 +28,7 @@ EXPORTS = (
     "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
     "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
     "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head", "dllmc_set_policy",
+    "dllmc_probe_copy", "dllmc_probe_read", "dllmc_probe_mfma",
 )
 NUM_KERNEL_CLASSES = 13
 
@@ -132,6 +133,12 @@ def lib() -> C.CDLL:
         L.dllmc_plan_gemm_slices.argtypes = [C.c_int32] * 5 + [C.c_size_t]
         L.dllmc_set_gemm_tuning.restype = C.c_int
         L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 6
+        L.dllmc_probe_copy.restype = C.c_int
+        L.dllmc_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.dllmc_probe_read.restype = C.c_int
+        L.dllmc_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.dllmc_probe_mfma.restype = C.c_int
+        L.dllmc_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         _lib = L
     return _lib
 
@@ -372,3 +379,25 @@ def op_attention(dtype: str, q: torch.Tensor, k_cache: torch.Tensor, v_cache: to
                                     v_cache.data_ptr(), n, H_q, H_kv, d_h, out.data_ptr(),
                                     _ptr(scratch), _stream_handle()), "dllmc_op_attention")
     return out
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """dst = src with the library's plain copy kernel (achievable-bandwidth probe)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise DllmcError("probe_copy: size mismatch")
+    _check(lib().dllmc_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle()),
+           "dllmc_probe_copy")
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    _check(lib().dllmc_probe_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                  _stream_handle()), "dllmc_probe_read")
+
+
+def probe_mfma(iters: int, sink: torch.Tensor) -> float:
+    """Enqueues the MFMA loop; returns the flops of the launch."""
+    f = C.c_double(0.0)
+    _check(lib().dllmc_probe_mfma(iters, sink.data_ptr(), C.byref(f), _stream_handle()),
+           "dllmc_probe_mfma")
+    return f.value

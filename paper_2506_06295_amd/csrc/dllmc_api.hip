@@ -781,4 +781,34 @@ int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_
   return DLLMC_OK;
 }
 
+int dllmc_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || bytes < 16 || (bytes & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u) ||
+      (reinterpret_cast<uintptr_t>(dst) & 15u))
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_probe_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
+  if (!src || !sink || bytes < 16 || (bytes & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u) ||
+      (reinterpret_cast<uintptr_t>(sink) & 3u))
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  launch_probe_read(src, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(hip_stream));
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+int dllmc_probe_mfma(int32_t iters, float* sink, double* flops_out, void* hip_stream) {
+  if (iters < 1 || iters > (1 << 24) || !sink || (reinterpret_cast<uintptr_t>(sink) & 15u))
+    return DLLMC_EINVAL;
+  (void)hipGetLastError();
+  const double f = launch_probe_mfma(iters, sink, static_cast<hipStream_t>(hip_stream));
+  if (flops_out) *flops_out = f;
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
 }  // extern "C"

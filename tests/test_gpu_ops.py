@@ -204,3 +204,41 @@ def test_attention_matches_oracle(dtype, B, Mq, n, H_q, H_kv, d_h, split_keys):
         want = O.attention(grid(q[b], dtype), grid(k[b], dtype), grid(v[b], dtype), H_q, H_kv, d_h)
         e = rel_err(got[b], want)
         assert e < (1e-5 if dtype == "f32" else 1e-2), f"seq {b}: rel err {e:.3e}"
+
+
+# ------------------------------------------------------------------ achievable-peak probes
+@pytest.mark.parametrize("nbytes", [16, 16 * 12345, 1 << 24])
+def test_probe_copy_copies_and_probe_read_writes_nothing(nbytes):
+    r = np.random.default_rng(nbytes)
+    src = torch.from_numpy(r.integers(0, 256, nbytes, dtype=np.uint8)).cuda()
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    keep = src.clone()
+    binding.probe_copy(src, dst)
+    binding.probe_read(src, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, keep) and torch.equal(src, keep)
+    with pytest.raises(binding.DllmcError):
+        binding.probe_copy(src[:8], dst[:8])
+
+
+def test_probe_mfma_result_follows_the_instruction_layout():
+    """The loop's operands are small dyadic numbers, so its result is exact: 8 accumulators x
+    iters x (A @ B), with A, B and the result spread over the 64 lanes as the 16x16x32 MFMA
+    defines (A: row = lane % 16, k = 8 * (lane / 16) + i; B alike with the column; result:
+    row = 4 * (lane / 16) + i, column = lane % 16)."""
+    iters = 3
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    flops = binding.probe_mfma(iters, sink)
+    torch.cuda.synchronize()
+    A = np.zeros((16, 32))
+    Bm = np.zeros((32, 16))
+    for lane in range(64):
+        for i in range(8):
+            A[lane % 16, 8 * (lane // 16) + i] = ((lane + i) & 7) / 8.0
+            Bm[8 * (lane // 16) + i, lane % 16] = ((3 * lane + i) & 7) / 8.0
+    Cm = 8 * iters * (A @ Bm)
+    want = np.array([Cm[4 * (lane // 16) + i, lane % 16] for lane in range(64) for i in range(4)])
+    assert np.array_equal(sink.cpu().numpy().astype(np.float64), want)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flops == cus * 8 * 4 * iters * 8 * 2 * 16 * 16 * 32
