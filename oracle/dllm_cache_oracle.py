@@ -36,7 +36,9 @@ selection against a full sort by (score, index) with engineered ties; rho=1 /
 K_p=K_r=1 and refresh steps equal the uncached forward; a repeated input right
 after a refresh reproduces the output with all scores 1; cache rows outside the
 selected set stay bit-identical; MAC counts and cache bytes against the paper's
-closed forms.  The absolute activation values of an adaptive step have no
+closed forms; update ratios per layer: equal ratios reproduce the global one,
+each layer rewrites exactly its own share of rows, the linear allocation has
+the appendix table's end values and average.  The absolute activation values of an adaptive step have no
 printed worked example in the paper: beyond those invariants they are
 "parity unpinned".
 """
@@ -189,6 +191,19 @@ def num_selected(rho: float, L_r: int) -> int:
     return int(math.floor(float(rho) * L_r + 1e-6))
 
 
+def linear_rho_allocation(T: int, first: float, last: float) -> List[float]:
+    """Update ratio per layer for the cross-layer allocation study (appendix table
+    "Cross-layer update ratio allocation"): the table gives the two end values of a
+    front-heavy and of a back-heavy allocation with a common average; read here as a straight
+    line over the layer index, rho_l = first + (last - first) * l / (T - 1), whose average is
+    (first + last) / 2."""
+    if T < 1:
+        raise ValueError("need at least one layer")
+    if T == 1:
+        return [0.5 * (first + last)]
+    return [first + (last - first) * l / (T - 1) for l in range(T)]
+
+
 def bottom_k(scores: np.ndarray, k: int) -> np.ndarray:
     """Indices of the k lowest scores; equal scores go to the lower index.
 
@@ -276,8 +291,11 @@ class CachedDenoiser:
                  L_p: int, L_r: int, rho: float, K_p: int, K_r: int,
                  storage: str = "f64", dtype=np.float64, metric: str = "cosine",
                  selection: str = "verify", v_update: str = "all", seed: int = 0,
-                 source: str = "v"):
-        """metric / selection / v_update / source pick the variants the paper compares with its
+                 source: str = "v", rho_layers: Optional[Sequence[float]] = None):
+        """rho_layers, if given, replaces rho layer by layer (the paper's selection is local to a
+        layer, appendix "Layer-wise token selection"; its cross-layer study gives layers
+        different ratios): layer l recomputes floor(rho_layers[l] * L_r) response rows.
+        metric / selection / v_update / source pick the variants the paper compares with its
         default (cosine V-verify, whole-V overwrite): metric "l2" (appendix "Impact of
         Similarity Metric"), selection "random" (Sec. 4.3), v_update "selected" (appendix
         "Design Choice Between Full V-Cache Overwrite and Selective Update": only the selected
@@ -297,6 +315,12 @@ class CachedDenoiser:
         self.B, self.L_p, self.L_r, self.n = B, L_p, L_r, L_p + L_r
         self.rho, self.K_p, self.K_r = rho, K_p, K_r
         self.k_sel = num_selected(rho, L_r)
+        if rho_layers is None:
+            self.k_layers = [self.k_sel] * model.T
+        else:
+            if len(rho_layers) != model.T or any(not (0.0 <= r <= 1.0) for r in rho_layers):
+                raise ValueError("need one ratio in [0, 1] per layer")
+            self.k_layers = [num_selected(r, L_r) for r in rho_layers]
         self.storage, self.dtype = storage, dtype
         self._st = _store_fn(storage)
         T, n = model.T, self.n
@@ -362,9 +386,9 @@ class CachedDenoiser:
                         s = l2_scores(T_new[resp_in_C], cache[b, L_p:])
                     else:
                         s = cosine_scores(T_new[resp_in_C], cache[b, L_p:])
-                    S = bottom_k(s, self.k_sel)
+                    S = bottom_k(s, self.k_layers[l])
                     rep.scores[l][b] = s
-                    rep.gaps[l][b] = boundary_gap(s, self.k_sel)
+                    rep.gaps[l][b] = boundary_gap(s, self.k_layers[l])
                     if on_layer is not None:
                         alt = on_layer(l, b, s, S)
                         if alt is not None:

@@ -161,3 +161,72 @@ def test_k_verify_with_every_row_selected_equals_the_default():
         ob, _ = b.step(sched.hidden_in(i).astype(np.float64), i)
         assert np.allclose(oa, ob, rtol=1e-12, atol=1e-12)
     assert a.macs == b.macs
+
+
+# ---- update ratio per layer (appendix "Layer-wise token selection" / cross-layer allocation) ----
+def test_linear_allocation_matches_the_table_ends_and_budget():
+    for first, last in ((0.375, 0.125), (0.125, 0.375)):
+        for T in (2, 3, 28, 32):
+            r = O.linear_rho_allocation(T, first, last)
+            assert len(r) == T and r[0] == first and r[-1] == pytest.approx(last)
+            assert np.mean(r) == pytest.approx(0.25)                 # the table's common budget
+            steps = np.diff(r)
+            assert np.allclose(steps, steps[0]) and np.sign(steps[0]) == np.sign(last - first)
+    assert O.linear_rho_allocation(1, 0.375, 0.125) == [0.25]
+    assert O.linear_rho_allocation(5, 0.25, 0.25) == [0.25] * 5
+    # the front-heavy and the back-heavy allocation are each other's reversal
+    a, b = O.linear_rho_allocation(32, 0.375, 0.125), O.linear_rho_allocation(32, 0.125, 0.375)
+    assert np.allclose(a, b[::-1])
+
+
+def test_equal_ratios_per_layer_reproduce_the_global_ratio():
+    cfg = small_cfg(T=3, K_p=4, K_r=3, L_r=16, rho=0.25)
+    ws = I.all_weights(cfg)
+    a, b = make(cfg, ws, rho_layers=[0.25] * 3), make(cfg, ws)
+    sched = I.TokenSchedule(cfg, stress=True)
+    for i in range(6):
+        oa, ra = a.step(sched.hidden_in(i).astype(np.float64), i)
+        ob, rb = b.step(sched.hidden_in(i).astype(np.float64), i)
+        assert np.array_equal(oa, ob)
+        assert all(np.array_equal(x[0], y[0]) for x, y in zip(ra.selected, rb.selected))
+    with pytest.raises(ValueError):
+        make(cfg, ws, rho_layers=[0.25, 0.25])
+    with pytest.raises(ValueError):
+        make(cfg, ws, rho_layers=[0.25, 1.5, 0.0])
+
+
+def test_each_layer_recomputes_its_own_share():
+    cfg = small_cfg(T=4, K_p=8, K_r=8, L_r=16, rho=0.25)
+    ws = I.all_weights(cfg)
+    ratios = [0.5, 0.0, 1.0, 0.13]
+    den = make(cfg, ws, rho_layers=ratios)
+    ref_full = make(cfg, ws, rho=1.0)           # recomputes every response row at every layer
+    sched = I.TokenSchedule(cfg, stress=True)
+    for d in (den, ref_full):
+        d.step(sched.hidden_in(0).astype(np.float64), 0)
+    before = {name: [c.copy() for c in getattr(den, name)] for name in ("K", "V", "AttnOut", "FFNOut")}
+    macs0 = den.macs
+    _, rep = den.step(sched.hidden_in(1).astype(np.float64), 1)
+    ref_full.step(sched.hidden_in(1).astype(np.float64), 1)
+    Lp, Lr = cfg.L_p, cfg.L_r
+    assert [rep.selected[l][0].size for l in range(4)] == [8, 0, 16, 2]   # floor(rho_l * 16)
+    for l in range(4):
+        S = rep.selected[l][0]
+        rest = np.setdiff1d(np.arange(Lr), S)
+        for name in ("K", "AttnOut", "FFNOut"):
+            now, old = getattr(den, name)[l][0, Lp:], before[name][l][0, Lp:]
+            assert np.array_equal(now[rest], old[rest])
+            assert not np.any(np.all(now[S] == old[S], axis=1))
+        # V is overwritten for the whole response at every layer, whatever its ratio
+        assert not np.any(np.all(den.V[l][0, Lp:] == before["V"][l][0, Lp:], axis=1))
+    # layer 0 sees the step's input: its selected rows' Keys equal a full recomputation's
+    S0 = rep.selected[0][0]
+    assert np.array_equal(den.K[0][0, Lp + S0], ref_full.K[0][0, Lp + S0])
+    # multiply-accumulates of the step: V for all rows plus Q, K, attention, O, FFN per selected row
+    mo = den.model
+    per_row = mo.d * (mo.d_q + mo.d_kv) + 2 * cfg.n * mo.d_q + mo.d_q * mo.d + 3 * mo.d * mo.m
+    want = sum(Lr * mo.d * mo.d_kv + k * per_row for k in (8, 0, 16, 2))
+    assert den.macs - macs0 == want
+    # a refresh step ignores the ratios
+    _, rep8 = den.step(sched.hidden_in(8 % cfg.steps).astype(np.float64), 8)
+    assert all(rep8.selected[l][0].size == Lr for l in range(4))
