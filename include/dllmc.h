@@ -105,6 +105,17 @@ int32_t dllmc_num_selected(const dllmc_ctx* ctx);
 int dllmc_set_policy(dllmc_ctx* ctx, int32_t source, int32_t metric, int32_t selection,
                      int32_t v_update, uint32_t seed);
 
+/* Update ratio per layer (appendix "Layer-wise token selection": the selection is local to a
+ * layer; its cross-layer study gives layers different ratios under one average budget): on an
+ * adaptive step layer l recomputes floor(rho_layers[l] * L_r) response rows per sequence.
+ * rho_layers: HOST array of n_layers floats in [0, 1], copied; NULL returns to the single ratio
+ * given at dllmc_create.  n_layers must equal the model's.  Takes effect at the next
+ * dllmc_step.  With it, dllmc_step's n_sel reports the largest count over the layers and the
+ * first dllmc_layer_num_selected(ctx, l) entries of sel_idx[l][b][:] are valid on an adaptive
+ * step.  DLLMC_EINVAL on a ratio outside [0, 1] (nothing is changed then) or a wrong count. */
+int dllmc_set_layer_rho(dllmc_ctx* ctx, const float* rho_layers, int32_t n_layers);
+int32_t dllmc_layer_num_selected(const dllmc_ctx* ctx, int32_t layer);
+
 /* One denoising step (Sec. 3.2 "Iterative Steps").
  *   hidden_in  device [B, L_p+L_r, d], model dtype: embedded tokens of this step.
  *   step_idx   0 for the first call (fills both caches), then strictly increasing; passing 0

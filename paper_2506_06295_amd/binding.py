@@ -28,7 +28,7 @@ EXPORTS = (
     "dllmc_set_gemm_tuning", "dllmc_op_attention_scratch_bytes", "dllmc_plan_gemm_slices",
     "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
     "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head", "dllmc_set_policy",
-    "dllmc_probe_copy", "dllmc_probe_read", "dllmc_probe_mfma",
+    "dllmc_set_layer_rho", "dllmc_layer_num_selected", "dllmc_probe_copy", "dllmc_probe_read", "dllmc_probe_mfma",
 )
 NUM_KERNEL_CLASSES = 13
 
@@ -133,6 +133,10 @@ def lib() -> C.CDLL:
         L.dllmc_plan_gemm_slices.argtypes = [C.c_int32] * 5 + [C.c_size_t]
         L.dllmc_set_gemm_tuning.restype = C.c_int
         L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 6
+        L.dllmc_set_layer_rho.restype = C.c_int
+        L.dllmc_set_layer_rho.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32]
+        L.dllmc_layer_num_selected.restype = C.c_int32
+        L.dllmc_layer_num_selected.argtypes = [C.c_void_p, C.c_int32]
         L.dllmc_probe_copy.restype = C.c_int
         L.dllmc_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.dllmc_probe_read.restype = C.c_int
@@ -217,6 +221,20 @@ class CachedDenoiser:
                                       {"verify": 0, "random": 1}[selection],
                                       {"all": 0, "selected": 1}[v_update], seed & 0xFFFFFFFF),
                "dllmc_set_policy")
+
+    def set_layer_rho(self, rho_layers) -> None:
+        """One update ratio per layer, or None for the single ratio given at creation."""
+        if rho_layers is None:
+            _check(lib().dllmc_set_layer_rho(self._h, None, 0), "dllmc_set_layer_rho")
+            return
+        arr = (C.c_float * len(rho_layers))(*[float(r) for r in rho_layers])
+        _check(lib().dllmc_set_layer_rho(self._h, arr, len(rho_layers)), "dllmc_set_layer_rho")
+
+    def layer_num_selected(self, layer: int) -> int:
+        k = lib().dllmc_layer_num_selected(self._h, layer)
+        if k < 0:
+            raise DllmcError("dllmc_layer_num_selected: invalid argument")
+        return k
 
     def read_cache(self, layer: int, which: int) -> torch.Tensor:
         width = self.d_kv if which < 2 else self.d

@@ -1,5 +1,6 @@
 // Host side of libdllmc.so: the C ABI, the context (workspace carving, cache schedule of
 // paper Sec. 3.2) and the per-layer launch sequence of one denoising step.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -110,6 +111,7 @@ struct dllmc_ctx {
   bool random_sel = false;
   bool v_selected_only = false;
   uint32_t seed = 0;
+  std::vector<int> k_layer;  // rows recomputed per sequence on adaptive steps, per layer
 
   // optional per-kernel timing with HIP events on the context's stream
   bool profiling = false;
@@ -197,6 +199,7 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
   // floor(rho * |y|), |y| = response length (Sec. 3.2.2)
   c->k_sel = static_cast<int>(std::floor(static_cast<double>(rho) * L_r + 1e-6));
   if (c->k_sel > L_r) c->k_sel = L_r;
+  c->k_layer.assign(model->n_layers, c->k_sel);
   c->st = static_cast<hipStream_t>(hip_stream);
   c->last_step = -1;
   c->lay = lay;
@@ -226,6 +229,27 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
 }
 
 int32_t dllmc_num_selected(const dllmc_ctx* ctx) { return ctx ? ctx->k_sel : DLLMC_EINVAL; }
+
+int32_t dllmc_layer_num_selected(const dllmc_ctx* ctx, int32_t layer) {
+  if (!ctx || layer < 0 || layer >= ctx->m.n_layers) return DLLMC_EINVAL;
+  return ctx->k_layer[layer];
+}
+
+int dllmc_set_layer_rho(dllmc_ctx* c, const float* rho_layers, int32_t n_layers) {
+  if (!c) return DLLMC_EINVAL;
+  if (!rho_layers) {
+    c->k_layer.assign(c->m.n_layers, c->k_sel);
+    return DLLMC_OK;
+  }
+  if (n_layers != c->m.n_layers) return DLLMC_EINVAL;
+  for (int l = 0; l < n_layers; ++l)
+    if (!(rho_layers[l] >= 0.f && rho_layers[l] <= 1.f)) return DLLMC_EINVAL;
+  for (int l = 0; l < n_layers; ++l) {
+    int k = static_cast<int>(std::floor(static_cast<double>(rho_layers[l]) * c->L_r + 1e-6));
+    c->k_layer[l] = k > c->L_r ? c->L_r : k;
+  }
+  return DLLMC_OK;
+}
 
 int dllmc_set_policy(dllmc_ctx* c, int32_t source, int32_t metric, int32_t selection,
                      int32_t v_update, uint32_t seed) {
@@ -257,11 +281,15 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   const bool Rf = (step_idx % c->K_r == 0);
   const int carried_per_seq = (P ? L_p : 0) + L_r;
   const int Mc = B * carried_per_seq;
-  const int sel_per_seq = Rf ? L_r : c->k_sel;
-  const int per_seq = (P ? L_p : 0) + sel_per_seq;  // recomputed rows per sequence
-  const int M_R = B * per_seq;
   const int sel_off = P ? L_p : 0;
-  if (n_sel) *n_sel = sel_per_seq;
+  // response rows recomputed per sequence at layer l, and with the refreshed prompt rows
+  auto sel_of = [&](int l) { return Rf ? L_r : c->k_layer[l]; };
+  auto per_seq_of = [&](int l) { return sel_off + sel_of(l); };
+  if (n_sel) {
+    int mx = 0;
+    for (int l = 0; l < T; ++l) mx = std::max(mx, sel_of(l));
+    *n_sel = mx;
+  }
 
   const RowKernelArgs ra{dt, n, L_p, d, m.rms_eps};
   int* carried = c->at<int>(c->lay.off_carried);
@@ -297,9 +325,9 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   {
     Timed t(c, DLLMC_KC_LISTS, 0, 0);
     launch_iota_rows(carried, nullptr, B, n, P ? 0 : L_p, carried_per_seq, carried_per_seq, 0, st);
-    if (P) launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq, 0, st);
+    if (P) launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq_of(0), 0, st);
     if (Rf) {
-      launch_iota_rows(rows_R, inv, B, n, L_p, L_r, per_seq, sel_off, st);
+      launch_iota_rows(rows_R, inv, B, n, L_p, L_r, per_seq_of(0), sel_off, st);
       if (sel_idx) launch_fill_sel_identity(sel_idx, T * B, L_r, st);
     }
   }
@@ -310,6 +338,13 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
 
   for (int l = 0; l < T; ++l) {
     const dllmc_layer_weights& w = c->layers[l];
+    const int k_l = sel_of(l), per_seq = per_seq_of(l), M_R = B * per_seq;
+    if (P && l > 0 && per_seq != per_seq_of(l - 1)) {
+      // the compact list of recomputed rows is laid out with this layer's row count per
+      // sequence: the refreshed prompt rows move to their new places
+      Timed t(c, DLLMC_KC_LISTS, 0, 0);
+      launch_iota_rows(rows_R, inv, B, n, 0, L_p, per_seq, 0, st);
+    }
     void* Kc = c->cache(0, l);
     void* Vc = c->cache(1, l);
     // Verify: the verified projection (V; K for the K-verify variant) for every carried row,
@@ -338,9 +373,9 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
                           defer_v ? abuf : nullptr, st);
     }
     if (!Rf) {
-      Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + c->k_sel * 8.0 + L_r * 4.0), 0);
+      Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + k_l * 8.0 + L_r * 4.0), 0);
       if (c->random_sel) launch_random_scores(c->seed, step_idx, l, B, L_r, sc, st);
-      launch_select(sc, B, L_r, c->k_sel,
+      launch_select(sc, B, L_r, k_l,
                     sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
                     per_seq, sel_off, inv, n, L_p, st);
       if (defer_v)

@@ -68,6 +68,9 @@ def make_pair(cfg: I.Config, weights: List[Dict[str, np.ndarray]], **over):
     policy = {k: over[k] for k in ("metric", "selection", "v_update", "seed", "source") if k in over}
     if policy:
         gpu.set_policy(**policy)
+    if over.get("rho_layers") is not None:
+        gpu.set_layer_rho(over["rho_layers"])
+        policy = dict(policy, rho_layers=over["rho_layers"])
     ora = O.CachedDenoiser(oracle_model(cfg),
                            [{k: np.asarray(v, dtype=np.float64) for k, v in w.items()} for w in weights],
                            cfg.B, cfg.L_p, cfg.L_r, rho, K_p, K_r,
@@ -96,7 +99,8 @@ def selection_checker(cfg, gpu, ora, i: int, n_sel: int, stats: ParityStats):
     """After the GPU ran step i: checks the integer part of its selections and returns
     (sel [T, B, n_sel], on_layer callback for the oracle's step) implementing the rule above."""
     sel = gpu.sel_idx[:, :, :n_sel].cpu().numpy().astype(np.int64)
-    k = ora.k_sel
+    refresh = i % ora.K_r == 0
+    ks = [cfg.L_r if refresh else ora.k_layers[l] for l in range(cfg.T)]   # valid entries per layer
     tol = gap_tol(cfg)
     gpu_scores = None
     if i % ora.K_r != 0:
@@ -106,11 +110,12 @@ def selection_checker(cfg, gpu, ora, i: int, n_sel: int, stats: ParityStats):
         # integer part of the decision: exact bottom-k of the GPU's own scores
         for l in range(cfg.T):
             for b in range(cfg.B):
-                want = O.bottom_k(gpu_scores[l, b].astype(np.float64), k)
-                assert sel[l, b].tolist() == want.tolist(), f"step {i} layer {l} seq {b}: select kernel"
+                want = O.bottom_k(gpu_scores[l, b].astype(np.float64), ks[l])
+                assert sel[l, b, :ks[l]].tolist() == want.tolist(), f"step {i} layer {l} seq {b}: select kernel"
 
     def on_layer(l, b, s, own):
-        got = sel[l, b]
+        k = ks[l]
+        got = sel[l, b, :k]
         gap = O.boundary_gap(s, k)
         stats.gaps.append(gap)
         band = tol
@@ -140,15 +145,15 @@ def selection_checker(cfg, gpu, ora, i: int, n_sel: int, stats: ParityStats):
 
 
 def check_selection_shape(cfg, ora, rep, sel, n_sel: int):
-    k = ora.k_sel
     if rep.response_refresh:
         assert n_sel == cfg.L_r
         assert np.array_equal(sel, np.broadcast_to(np.arange(cfg.L_r), sel.shape))
     else:
-        assert n_sel == k
-        if k:
-            assert np.all(np.diff(sel, axis=-1) > 0), "indices must be ascending"
-            assert sel.min() >= 0 and sel.max() < cfg.L_r
+        assert n_sel == max(ora.k_layers)
+        for l, k in enumerate(ora.k_layers):
+            if k:
+                assert np.all(np.diff(sel[l, :, :k], axis=-1) > 0), "indices must be ascending"
+                assert sel[l, :, :k].min() >= 0 and sel[l, :, :k].max() < cfg.L_r
 
 
 def run_step_pair(cfg, gpu, ora, hidden_in: np.ndarray, i: int, stats: ParityStats):

@@ -278,3 +278,51 @@ def test_call_order_and_argument_errors():
         PU.make_pair(cfg, ws, rho=1.5)
     with pytest.raises(binding.DllmcError):
         PU.make_pair(cfg, ws, K_r=0)
+
+
+LAYER_RHO_CASES = [
+    (I.CONFIGS["toy"].replace(K_p=3, K_r=4), [0.5, 0.125]),
+    (MINI_DREAM, [0.125, 0.375]),                                    # K_p = 5, K_r = 4: step 5 refreshes the prompt only
+    (MINI_LLADA.replace(T=4, K_p=3, K_r=4), [1.0, 0.0, 0.37, 0.05]),  # a layer that recomputes nothing, one everything
+    (MINI_LLADA.replace(T=4, K_p=3, K_r=4), O.linear_rho_allocation(4, 0.375, 0.125)),
+]
+
+
+@pytest.mark.parametrize("cfg,ratios", LAYER_RHO_CASES, ids=lambda v: v.name if hasattr(v, "name") else "-".join(f"{r:.3g}" for r in v))
+def test_update_ratio_per_layer(cfg, ratios):
+    """Every layer recomputes its own floor(rho_l * L_r) rows (cross-layer allocation study of
+    the appendix); whole schedules incl. steps that refresh the prompt but not the response,
+    where the compact row list changes its layout from layer to layer."""
+    gpu, ora, st = run_schedule(cfg, stress=True, rho_layers=ratios)
+    report(f"{cfg.name} rho_layers={ratios}", st)
+    for l, r in enumerate(ratios):
+        assert gpu.layer_num_selected(l) == O.num_selected(r, cfg.L_r) == ora.k_layers[l]
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= (1e-4 if cfg.dtype == "f32" else 2e-2)
+    PU.compare_caches(cfg, gpu, ora, 1e-4 if cfg.dtype == "f32" else 2e-2)
+    gpu.close()
+
+
+def test_update_ratio_per_layer_arguments_and_reset():
+    cfg = MINI_LLADA.replace(steps=4)
+    ws = I.all_weights(cfg)
+    gpu, ora = PU.make_pair(cfg, ws)
+    k = gpu.num_selected
+    for bad in ([0.25, 0.25], [0.25, 0.25, 0.25, 0.25], [0.25, 1.01, 0.25], [0.25, -0.1, 0.25],
+                [0.25, float("nan"), 0.25]):
+        with pytest.raises(binding.DllmcError):
+            gpu.set_layer_rho(bad)
+        assert [gpu.layer_num_selected(l) for l in range(cfg.T)] == [k] * cfg.T   # nothing changed
+    gpu.set_layer_rho([0.5, 0.0, 1.0])
+    assert [gpu.layer_num_selected(l) for l in range(cfg.T)] == [40, 0, 80]
+    gpu.set_layer_rho(None)
+    assert [gpu.layer_num_selected(l) for l in range(cfg.T)] == [k] * cfg.T
+    with pytest.raises(binding.DllmcError):
+        gpu.layer_num_selected(cfg.T)
+    # after the reset the schedule is the plain one again
+    sched = I.TokenSchedule(cfg, stress=True)
+    st = PU.ParityStats()
+    for i in range(cfg.steps):
+        PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, st)
+    assert st.failed == 0 and st.worst_rel <= 2e-2
+    gpu.close()
