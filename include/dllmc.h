@@ -231,9 +231,10 @@ int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_
                   void* scratch, int32_t* x0, float* conf, void* hip_stream);
 
 /* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
- * that knob unchanged): nw / nw_dual wavefronts per workgroup (4|8) of the single-matrix and
- * of the fused gate/up kernel (nw_dual + 100: the wavefronts of a workgroup form two groups
- * that each walk one half of the contraction range), force_s number of contraction slices
+ * that knob unchanged): nw wavefronts per workgroup (4|8) of the single-matrix kernel; nw_dual
+ * shape of the fused gate/up kernel: 4|8 wavefronts in one group, or 100 + (4|6|8): the
+ * wavefronts form two groups that each walk one half of the contraction range (default 106:
+ * 48 columns of each matrix per workgroup); force_s number of contraction slices
  * (0 = automatic), target_wg
  * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
  * from which the 128 x 128 / the 256 x 256 LDS-direct tile kernel replaces the

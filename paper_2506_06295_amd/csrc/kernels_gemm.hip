@@ -134,6 +134,8 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 //             its accumulators over through LDS at the end and the first adds them (its own
 //             sum first).  Doubles the wavefronts, and with them the loads in flight, of a
 //             launch that cannot split the contraction over workgroups (DUAL).
+// N only has to be a multiple of 16: a ragged last tile is allowed, and with it any number of
+// column wavefronts.
 template <int NW, int KC, int DUAL, int KH>
 __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
@@ -141,10 +143,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
   constexpr int LS = KC + 8;                      // LDS row stride: rows start 4 banks apart
   constexpr int CPR = KC / 8;                     // 16-byte chunks per activation row and phase
-  constexpr int NCH = KH * 64 * CPR / (NW * 64);  // chunks staged per thread and phase
+  constexpr int TOT = KH * 64 * CPR;              // chunks of the workgroup's activation tiles
+  constexpr int NCH = (TOT + NW * 64 - 1) / (NW * 64);  // chunks staged per thread and phase
+  constexpr bool EVEN = TOT % (NW * 64) == 0;     // otherwise the last chunk of some threads is void
   constexpr int NB = DUAL ? 2 : 1;
   constexpr int NWC = NW / KH;                    // wavefronts side by side over the columns
-  static_assert((KH * 64 * CPR) % (NW * 64) == 0 && NCH >= 1, "staging must divide evenly");
   static_assert(NW % KH == 0, "wavefront groups must be equal");
   __shared__ __attribute__((aligned(16))) bf16_t As[2][KH][64 * LS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
@@ -157,7 +160,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KH * KC
   const int hlen = klen / KH;                          // contraction range of one group
   const int nph = hlen / KC;
-  const int ncol = col_tile * (16 * NWC) + wcol * 16 + ln;  // < N: N % (16*NWC) == 0
+  // this wavefront's block of 16 columns; in a ragged last tile the blocks beyond N / 16 repeat
+  // the last one (same loads, same barriers) and store nothing
+  const int cb = col_tile * NWC + wcol;
+  const bool active = cb * 16 < N;
+  const int ncol = (active ? cb : N / 16 - 1) * 16 + ln;
   const bf16_t* wp[NB];
   if (DUAL) {
     wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + kh * hlen + lg * 8;
@@ -169,13 +176,15 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   // the activation chunks this thread stages: same (group, row, chunk) in every phase
   const bf16_t* asrc[NCH];
   int adst[NCH];
-  bool aval[NCH];
+  bool aval[NCH], ain[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const int e = threadIdx.x + j * NW * 64;
+    int e = threadIdx.x + j * NW * 64;
+    ain[j] = EVEN || e < TOT;
+    if (!ain[j]) e = 0;
     const int h = e / (64 * CPR), r = (e / CPR) % 64, c = e % CPR;
     const int m = m0 + r;
-    aval[j] = m < M;
+    aval[j] = ain[j] && m < M;
     const int row = aval[j] ? (rows ? rows[m] : m) : 0;
     asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + h * hlen + c * 8;
     adst[j] = h * 64 * LS + r * LS + c * 8;
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   for (int j = 0; j < NCH; ++j) {
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j]);
-    *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = v;
+    if (ain[j]) *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = v;
   }
   // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
   constexpr int NS = KC / 128;
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     if (more) {
 #pragma unroll
       for (int j = 0; j < NCH; ++j)
-        *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][0][adst[j]]) = av[j];
+        if (ain[j]) *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][0][adst[j]]) = av[j];
     }
     __syncthreads();
   }
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
             red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
     }
     __syncthreads();
-    if (kh > 0) return;
+    if (kh > 0 || !active) return;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
@@ -274,6 +283,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
           acc[b][mb][i] += red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane];
   }
 
+  if (!active) return;
   if (DUAL) {
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -515,7 +525,10 @@ void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, 
 namespace {
 struct GemmTuning {
   int nw = 8;          // wavefronts per workgroup (4 or 8) of the single-matrix kernel
-  int nw_dual = 108;   // fused gate/up kernel: 8 wavefronts, two groups over the contraction range
+  int nw_dual = 106;   // fused gate/up kernel: 6 wavefronts in two groups over the contraction
+                       // range (+100), i.e. 48 columns of each matrix per workgroup: the
+                       // narrowest tile that still amortises the activation tile measured
+                       // fastest at both FFN widths (12288: one workgroup per CU)
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
   int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
@@ -547,7 +560,8 @@ void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
   if (nw == 4 || nw == 8) g_tune.nw = nw;
-  if (nw_dual == 4 || nw_dual == 8 || nw_dual == 104 || nw_dual == 108) g_tune.nw_dual = nw_dual;
+  if (nw_dual == 4 || nw_dual == 8 || nw_dual == 104 || nw_dual == 106 || nw_dual == 108)
+    g_tune.nw_dual = nw_dual;
   if (force_s >= 0) g_tune.force_s = force_s;
   if (target_wg > 0) g_tune.target_wg = target_wg;
 }
@@ -681,10 +695,11 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
                         const void* w_gate, const void* w_up, int m, int K, void* u,
                         hipStream_t st) {
   if (M <= 0 || m <= 0) return true;
-  const int NW = g_tune.nw_dual % 100;  // wavefronts per workgroup
   const int KC = (K % 256 == 0) ? 256 : 128;
   // two wavefront groups over the two halves of K when the halves are whole phases
   const int KH = (g_tune.nw_dual >= 100 && K % (2 * KC) == 0) ? 2 : 1;
+  int NW = g_tune.nw_dual % 100;  // wavefronts per workgroup
+  if (KH == 1 && NW == 6) NW = 3;  // the two-group shape without the split: one group of its width
   const int BN = 16 * NW / KH;
   if (M >= g_tune.tile_min_m && stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && K % kFatK == 0) {
     // many rows: the LDS-direct tile kernels with paired gate/up column blocks, one slice
@@ -704,8 +719,8 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
       return true;
     }
   }
-  if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % BN == 0) || M > 128) return false;
-  const dim3 grid(m / BN, (M + 63) / 64, 1);
+  if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % 16 == 0) || M > 128) return false;
+  const dim3 grid((m + BN - 1) / BN, (M + 63) / 64, 1);
   t_last_stream = true;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
@@ -713,14 +728,13 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   bf16_t* uo = static_cast<bf16_t*>(u);
 #define DLLMC_GD(NWv, KCv, KHv) \
   launch_stream<NWv, KCv, 1, KHv>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
-  if (NW == 8 && KH == 2) {
-    if (KC == 256) DLLMC_GD(8, 256, 2); else DLLMC_GD(8, 128, 2);
-  } else if (NW == 8) {
-    if (KC == 256) DLLMC_GD(8, 256, 1); else DLLMC_GD(8, 128, 1);
-  } else if (KH == 2) {
-    if (KC == 256) DLLMC_GD(4, 256, 2); else DLLMC_GD(4, 128, 2);
-  } else {
-    if (KC == 256) DLLMC_GD(4, 256, 1); else DLLMC_GD(4, 128, 1);
+  switch (NW * 10 + KH) {
+    case 62: if (KC == 256) DLLMC_GD(6, 256, 2); else DLLMC_GD(6, 128, 2); break;
+    case 82: if (KC == 256) DLLMC_GD(8, 256, 2); else DLLMC_GD(8, 128, 2); break;
+    case 31: if (KC == 256) DLLMC_GD(3, 256, 1); else DLLMC_GD(3, 128, 1); break;
+    case 81: if (KC == 256) DLLMC_GD(8, 256, 1); else DLLMC_GD(8, 128, 1); break;
+    case 42: if (KC == 256) DLLMC_GD(4, 256, 2); else DLLMC_GD(4, 128, 2); break;
+    default: if (KC == 256) DLLMC_GD(4, 256, 1); else DLLMC_GD(4, 128, 1); break;
   }
 #undef DLLMC_GD
   return true;

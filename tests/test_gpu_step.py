@@ -23,7 +23,7 @@ MINI_DREAM = I.Config("mini_dream", T=2, d=896, H_q=7, H_kv=1, d_h=128, m=2432, 
 MINI_LONG = I.Config("mini_long", T=2, d=512, H_q=4, H_kv=4, d_h=128, m=1536, B=1, L_p=700,
                      L_r=130, steps=5, rho=0.1, K_p=4, K_r=3, dtype="bf16", vocab=4096)
 
-DEFAULT_NW_DUAL = 108  # the library's default shape of the fused gate/up kernel
+DEFAULT_NW_DUAL = 106  # the library's default shape of the fused gate/up kernel
 
 
 def run_schedule(cfg, stress=False, steps=None, **over):
@@ -86,7 +86,7 @@ def test_bf16_stress_schedule_exact_indices(cfg):
     gpu.close()
 
 
-@pytest.mark.parametrize("nw_dual", [4, 8, 104, 108])
+@pytest.mark.parametrize("nw_dual", [4, 8, 104, 106, 108])
 @pytest.mark.parametrize("cfg", [MINI_LLADA, MINI_LONG], ids=lambda c: c.name)
 def test_fused_gate_up_kernel_variants(cfg, nw_dual):
     """Every workgroup shape of the fused gate/up kernel (wavefronts per workgroup, one or two
