@@ -73,7 +73,7 @@ constexpr int kDH = 128;       // head width of the MFMA kernel
 constexpr int kVtStride = 40;  // 32 keys + 8 pad (bf16 elements) per transposed V row
 constexpr int kQT = 64;        // queries per workgroup: four wavefronts x 16
 constexpr int kPreload = 3;    // key ranges of up to this many 32-key blocks are fetched whole
-constexpr int kMaxKeySplit = 8;
+constexpr int kMaxKeySplit = 16;
 
 // Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; blockIdx.z
 // enumerates (sequence, key range).  All four wavefronts walk the same 32-key blocks, so a V
@@ -296,17 +296,18 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
 
 // out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.
 // One wavefront per (query, head), two dims per lane.
+template <int SLOTS>
 __global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ part, int KS, int H_q,
                                                    bf16_t* __restrict__ out) {
   const size_t qh = static_cast<size_t>(blockIdx.x);  // (b*Mq + iq)*H_q + a
   const float* w = part + qh * KS * (kDH + 2);
-  // All kMaxKeySplit slots are loaded before the first use (slots past KS re-read the last
+  // All SLOTS >= KS slots are loaded before the first use (slots past KS re-read the last
   // valid one and get weight zero): a loop over the runtime count would wait for each load.
   const int dim = threadIdx.x * 2;
-  float mr[kMaxKeySplit], lr[kMaxKeySplit];
-  float2 o[kMaxKeySplit];
+  float mr[SLOTS], lr[SLOTS];
+  float2 o[SLOTS];
 #pragma unroll
-  for (int r = 0; r < kMaxKeySplit; ++r) {
+  for (int r = 0; r < SLOTS; ++r) {
     const float* wr = w + min(r, KS - 1) * (kDH + 2);
     mr[r] = wr[kDH];
     lr[r] = wr[kDH + 1];
@@ -314,10 +315,10 @@ __global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ par
   }
   float M = -INFINITY;
 #pragma unroll
-  for (int r = 0; r < kMaxKeySplit; ++r) M = fmaxf(M, mr[r]);
+  for (int r = 0; r < SLOTS; ++r) M = fmaxf(M, mr[r]);
   float L = 0.f, o0 = 0.f, o1 = 0.f;
 #pragma unroll
-  for (int r = 0; r < kMaxKeySplit; ++r) {
+  for (int r = 0; r < SLOTS; ++r) {
     const float f = (r >= KS || mr[r] == -INFINITY) ? 0.f : exp2f(mr[r] - M);
     L += lr[r] * f;
     o0 += o[r].x * f;
@@ -355,7 +356,9 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     if (scratch != nullptr && base < 512) {
       KS = (512 + base - 1) / base;
       if (KS > kMaxKeySplit) KS = kMaxKeySplit;
-      if (KS > nblk / 2) KS = nblk / 2 > 0 ? nblk / 2 : 1;  // at least two blocks per range
+      // ranges of three blocks are fetched whole in one trip; shorter ones only add partial
+      // results to merge
+      if (KS > (nblk + 2) / 3) KS = (nblk + 2) / 3;
     }
     if ((nblk + KS - 1) / KS <= kPreload)
       hipLaunchKernelGGL(k_attn_mfma<true>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
@@ -363,8 +366,11 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     else
       hipLaunchKernelGGL(k_attn_mfma<false>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
                          H_q, H_kv, KS, oo, scratch);
-    if (KS > 1)
-      hipLaunchKernelGGL(k_attn_merge, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, H_q, oo);
+    if (KS > 8)
+      hipLaunchKernelGGL(k_attn_merge<kMaxKeySplit>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS,
+                         H_q, oo);
+    else if (KS > 1)
+      hipLaunchKernelGGL(k_attn_merge<8>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, H_q, oo);
     return;
   }
   const size_t lds = static_cast<size_t>(d_h + n) * sizeof(float);
