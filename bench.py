@@ -42,7 +42,7 @@ def step_kind(cfg, i):
     return "full" if P and R else "prompt+adaptive" if P else "response" if R else "adaptive"
 
 
-def cpu_baseline(cfg, dev_weights, hidden_host, sample_layers=2):
+def cpu_baseline(cfg, dev_weights, hidden_host, sample_layers=8):
     """The CPU oracle timed on the host cores: one step of each kind on `sample_layers` layers,
     scaled to the full depth and to the schedule's kind counts."""
     import numpy as np
