@@ -94,6 +94,11 @@ def main():
     ap.add_argument("--no-probes", action="store_true", help="skip the achievable-peak probes")
     ap.add_argument("--no-closed-loop", action="store_true",
                     help="skip the closed-loop generation leg (embedding, head, remasking)")
+    ap.add_argument("--rho", type=float, default=None, help="update ratio instead of the workload's")
+    ap.add_argument("--layer-rho", default="", help="first,last: update ratio per layer on a straight "
+                    "line from the first to the last layer (cross-layer allocation study)")
+    ap.add_argument("--policy", default="", help="variant of the paper's ablations, e.g. "
+                    "source=k,metric=l2,selection=random,v_update=selected,seed=1")
     ap.add_argument("--tune", default="", help="GEMM tuning knobs, e.g. nw=8,nw_dual=4,force_s=0,target_wg=256")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -110,6 +115,8 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     cfg = I.CONFIGS[args.config]
+    if args.rho is not None:
+        cfg = cfg.replace(rho=args.rho)
     if args.tune:
         binding.set_gemm_tuning(**{k: int(v) for k, v in (kv.split("=") for kv in args.tune.split(","))})
     K = args.steps if args.steps is not None else cfg.steps
@@ -129,6 +136,15 @@ def main():
     hidden = [torch.from_numpy(h).cuda().to(tdt).contiguous() for h in hidden_host]
     out = torch.empty_like(hidden[0])
     den = make_denoiser(binding, cfg, weights)
+    variant = {}
+    if args.policy:
+        variant = {k: (int(v) if k == "seed" else v) for k, v in (kv.split("=") for kv in args.policy.split(","))}
+        den.set_policy(**variant)
+    if args.layer_rho:
+        first, last = (float(v) for v in args.layer_rho.split(","))
+        ratios = [first + (last - first) * l / max(cfg.T - 1, 1) for l in range(cfg.T)]
+        den.set_layer_rho(ratios)
+        variant["layer_rho"] = [first, last]
 
     def run(count, start=0):
         for s in range(start, start + count):
@@ -164,7 +180,7 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} heads={cfg.H_q}/{cfg.H_kv}x{cfg.d_h} "
                                f"m={cfg.m} B={cfg.B} L_p={cfg.L_p} L_r={cfg.L_r} rho={cfg.rho} "
                                f"K_p={cfg.K_p} K_r={cfg.K_r} schedule={cfg.steps} steps",
-                   "step_kinds_timed": kinds_timed, "seed": cfg.seed},
+                   "step_kinds_timed": kinds_timed, "seed": cfg.seed, "variant": variant or None},
         "response_tokens_per_s": cfg.B * cfg.L_r * steps_per_s / cfg.steps,
         "token_rows_per_s": cfg.B * cfg.L_r * steps_per_s,
     }
