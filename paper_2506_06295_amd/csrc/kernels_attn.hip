@@ -84,7 +84,7 @@ constexpr int kMaxKeySplit = 16;
 // fetched whole before its first use; the other instantiation walks its range block by block
 // and, without the preloaded fragments, keeps its accumulators in ordinary registers.
 template <bool PRELOAD>
-__global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q, int Mq,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_attn_mfma(const bf16_t* __restrict__ q, int Mq,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
                                                    int H_kv, int KS, bf16_t* __restrict__ out,
