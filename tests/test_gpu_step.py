@@ -326,3 +326,46 @@ def test_update_ratio_per_layer_arguments_and_reset():
         PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, st)
     assert st.failed == 0 and st.worst_rel <= 2e-2
     gpu.close()
+
+
+def test_adaptive_step_replayed_from_a_captured_graph():
+    """dllmc_step only enqueues kernels on the context's stream (no allocation, no host
+    synchronisation, no memset), so a caller may capture it.  One adaptive step is captured
+    once and replayed for the following steps from a fixed input buffer, with eager work and
+    synchronisations between the replays; every replay must equal the eager schedule bit for
+    bit (caches included: they carry over from replay to replay)."""
+    cfg = MINI_LLADA.replace(K_p=1000, K_r=1000, steps=6)
+    ws = I.all_weights(cfg)
+    sched = I.TokenSchedule(cfg, stress=True)
+    hid = [PU.to_device(cfg, sched.hidden_in(i)) for i in range(cfg.steps)]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        eager, _ = PU.make_pair(cfg, ws)
+        want, want_sel = [], []
+        for i in range(cfg.steps):
+            out, n_sel = eager.step(hid[i], i)
+            want.append(out.clone())
+            want_sel.append(eager.sel_idx[:, :, :n_sel].clone())
+        s.synchronize()
+        gpu, _ = PU.make_pair(cfg, ws)
+        static_in = hid[0].clone()
+        out0, _ = gpu.step(static_in, 0)
+        s.synchronize()
+        assert torch.equal(out0, want[0])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        static_out, n_sel = gpu.step(static_in, 1)
+    for i in range(1, cfg.steps):
+        static_in.copy_(hid[i])
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(static_out, want[i]), f"replay {i}"
+        assert torch.equal(gpu.sel_idx[:, :, :n_sel], want_sel[i]), f"replay {i}: selection"
+        # eager work of the program between replays
+        _ = (static_out.float() * 2).sum().item()
+    pairs = [(gpu.read_cache(l, which), eager.read_cache(l, which)) for l in range(cfg.T) for which in range(4)]
+    torch.cuda.synchronize()   # the reads run on the contexts' stream
+    assert all(torch.equal(a, b) for a, b in pairs)
+    gpu.close()
+    eager.close()
