@@ -238,11 +238,15 @@ int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_
  * (0 = automatic), target_wg
  * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
  * from which the 128 x 128 / the 256 x 256 LDS-direct tile kernel replaces the
- * weight-streaming kernel.  Results are
+ * weight-streaming kernel; tall_max_m (default 128; 0 = off): from 128 on, launches of 65..128
+ * rows run the weight-streaming kernel with 128 rows per workgroup (weights streamed once
+ * instead of once per 64-row tile); from 256 on, launches of tile_min_m .. tall_max_m rows use
+ * it with 256 rows per workgroup instead of the 128 x 128 tiles.
+ * Results are
  * bit-reproducible for fixed settings; different settings change the float32 summation order
  * only. */
 int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
-                          int32_t tile_min_m, int32_t fat_min_m);
+                          int32_t tile_min_m, int32_t fat_min_m, int32_t tall_max_m);
 
 /* Host-only: the number of contraction-index slices the library would use for a gathered
  * linear map of M rows, N columns (the first N0 from one matrix), contraction length K, given a

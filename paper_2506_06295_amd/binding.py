@@ -132,7 +132,7 @@ def lib() -> C.CDLL:
         L.dllmc_plan_gemm_slices.restype = C.c_int32
         L.dllmc_plan_gemm_slices.argtypes = [C.c_int32] * 5 + [C.c_size_t]
         L.dllmc_set_gemm_tuning.restype = C.c_int
-        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 6
+        L.dllmc_set_gemm_tuning.argtypes = [C.c_int32] * 7
         L.dllmc_set_layer_rho.restype = C.c_int
         L.dllmc_set_layer_rho.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int32]
         L.dllmc_layer_num_selected.restype = C.c_int32
@@ -348,8 +348,9 @@ def op_head(dtype: str, hidden: torch.Tensor, final_norm_g: torch.Tensor, lm_hea
 
 
 def set_gemm_tuning(nw: int = -1, nw_dual: int = -1, force_s: int = -1, target_wg: int = -1,
-                    tile_min_m: int = -1, fat_min_m: int = -1) -> None:
-    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg, tile_min_m, fat_min_m),
+                    tile_min_m: int = -1, fat_min_m: int = -1, tall_max_m: int = -1) -> None:
+    _check(lib().dllmc_set_gemm_tuning(nw, nw_dual, force_s, target_wg, tile_min_m, fat_min_m,
+                                       tall_max_m),
            "dllmc_set_gemm_tuning")
 
 

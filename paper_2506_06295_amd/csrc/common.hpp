@@ -76,6 +76,7 @@ int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity);
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg);
 void gemm_set_tile_min_m(int m);
 void gemm_set_fat_min_m(int m);
+void gemm_set_tall_max_m(int m);
 // True when the most recent launch_gemm / launch_gemm_swiglu of this thread ran k_gemm_stream.
 bool gemm_last_was_stream();
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,

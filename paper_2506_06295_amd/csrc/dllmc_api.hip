@@ -542,10 +542,11 @@ int32_t dllmc_plan_gemm_slices(int32_t dtype, int32_t M, int32_t N, int32_t N0, 
 }
 
 int dllmc_set_gemm_tuning(int32_t nw, int32_t nw_dual, int32_t force_s, int32_t target_wg,
-                          int32_t tile_min_m, int32_t fat_min_m) {
+                          int32_t tile_min_m, int32_t fat_min_m, int32_t tall_max_m) {
   gemm_set_tuning(nw, nw_dual, force_s, target_wg);
   gemm_set_tile_min_m(tile_min_m);
   gemm_set_fat_min_m(fat_min_m);
+  gemm_set_tall_max_m(tall_max_m);
   return DLLMC_OK;
 }
 

@@ -136,26 +136,31 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 //             launch that cannot split the contraction over workgroups (DUAL).
 // N only has to be a multiple of 16: a ragged last tile is allowed, and with it any number of
 // column wavefronts.
-template <int NW, int KC, int DUAL, int KH>
+//   RB:       16-row blocks per workgroup (4: the 64 rows described above).  With RB = 8 / 16 a
+//             wavefront keeps the accumulators of 128 / 256 rows, so the weights of a launch
+//             with that many rows are streamed once instead of once per 64-row tile (phases of
+//             128 then, to fit the activation tiles in LDS).
+template <int NW, int KC, int DUAL, int KH, int RB = 4>
 __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, int N0, int N, int K,
     int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
   constexpr int LS = KC + 8;                      // LDS row stride: rows start 4 banks apart
   constexpr int CPR = KC / 8;                     // 16-byte chunks per activation row and phase
-  constexpr int TOT = KH * 64 * CPR;              // chunks of the workgroup's activation tiles
+  constexpr int R = 16 * RB;                      // activation rows per workgroup
+  constexpr int TOT = KH * R * CPR;               // chunks of the workgroup's activation tiles
   constexpr int NCH = (TOT + NW * 64 - 1) / (NW * 64);  // chunks staged per thread and phase
   constexpr bool EVEN = TOT % (NW * 64) == 0;     // otherwise the last chunk of some threads is void
   constexpr int NB = DUAL ? 2 : 1;
   constexpr int NWC = NW / KH;                    // wavefronts side by side over the columns
   static_assert(NW % KH == 0, "wavefront groups must be equal");
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][KH][64 * LS];
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][KH][R * LS];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int wcol = wave % NWC, kh = wave / NWC;
   int col_tile, row_tile;
   xcd_tile_map(col_tile, row_tile);
-  const int m0 = row_tile * 64;
+  const int m0 = row_tile * R;
   const int kbeg = blockIdx.z * k_per_slice;
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KH * KC
   const int hlen = klen / KH;                          // contraction range of one group
@@ -182,18 +187,18 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     int e = threadIdx.x + j * NW * 64;
     ain[j] = EVEN || e < TOT;
     if (!ain[j]) e = 0;
-    const int h = e / (64 * CPR), r = (e / CPR) % 64, c = e % CPR;
+    const int h = e / (R * CPR), r = (e / CPR) % R, c = e % CPR;
     const int m = m0 + r;
     aval[j] = ain[j] && m < M;
     const int row = aval[j] ? (rows ? rows[m] : m) : 0;
     asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + h * hlen + c * 8;
-    adst[j] = h * 64 * LS + r * LS + c * 8;
+    adst[j] = h * R * LS + r * LS + c * 8;
   }
-  f32x4 acc[NB][4];
+  f32x4 acc[NB][RB];
 #pragma unroll
   for (int b = 0; b < NB; ++b)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < RB; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
@@ -242,7 +247,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
       for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
+        for (int mb = 0; mb < RB; ++mb) {
           const bf16x8 af =
               *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + t * 128 + c * 32);
 #pragma unroll
@@ -267,26 +272,26 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
       for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
+            red[((wcol * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
     }
     __syncthreads();
     if (kh > 0 || !active) return;
 #pragma unroll
     for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+      for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          acc[b][mb][i] += red[((wcol * NB + b) * 16 + mb * 4 + i) * 64 + lane];
+          acc[b][mb][i] += red[((wcol * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane];
   }
 
   if (!active) return;
   if (DUAL) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + mb * 16 + lg * 4 + i;
@@ -298,7 +303,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   } else {
     float* Cs = C + static_cast<size_t>(blockIdx.z) * M * N;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + mb * 16 + lg * 4 + i;
@@ -532,17 +537,22 @@ struct GemmTuning {
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
   int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
+  int tall_max_m = 128;     // most rows the streaming kernel covers with one workgroup tile:
+                            // 65..128 rows run with 128 rows per workgroup when it is >= 128
+                            // (weights streamed once instead of once per 64-row tile); from
+                            // 256 on, launches of tile_min_m..tall_max_m rows use 256 rows per
+                            // workgroup instead of the 128 x 128 tiles (slower where measured)
   int tile_min_m = 192;     // activation rows from which the 128 x 128 LDS-direct kernel is used
                             // (off by default: the streaming kernel is faster at the sizes measured)
 } g_tune;
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int NW, int KC, int DUAL, int KH = 1>
+template <int NW, int KC, int DUAL, int KH = 1, int RB = 4>
 void launch_stream(dim3 grid, hipStream_t st, const bf16_t* A, int lda, const int* rows, int M,
                    const bf16_t* W0, const bf16_t* W1, int N0, int N, int K, int kps, float* C,
                    bf16_t* U) {
-  hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL, KH>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
+  hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL, KH, RB>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
                      W1, N0, N, K, kps, C, U);
 }
 
@@ -556,6 +566,7 @@ static thread_local bool t_last_stream = false;
 bool gemm_last_was_stream() { return t_last_stream; }
 
 void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
+void gemm_set_tall_max_m(int m) { if (m >= 0) g_tune.tall_max_m = m; }
 void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
@@ -568,7 +579,8 @@ void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
 
 // Which kernel, how many slices of the contraction index and how long a slice: pure host logic.
 struct GemmPlan {
-  int kind;  // 0 nothing fits, 1 plain, 2 streaming, 3 256x256 LDS-direct, 4 128x128 LDS-direct
+  int kind;  // 0 nothing fits, 1 plain, 2 streaming, 3 256x256 LDS-direct, 4 128x128 LDS-direct,
+             // 5 / 6 streaming with 256 / 128 rows per workgroup
   int S, kps, KC, nt, mt;
 };
 
@@ -615,6 +627,18 @@ GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int 
     p.S = (K + p.kps - 1) / p.kps;
     return p;
   }
+  if (M >= g_tune.tile_min_m && M <= g_tune.tall_max_m && g_tune.tall_max_m >= 256) {
+    p.kind = 5;
+    p.KC = 128;
+    p.mt = (M + 255) / 256;
+    p.nt = N / BN;
+    int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
+    S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
+    p.kps = ((K + S - 1) / S + p.KC - 1) / p.KC * p.KC;
+    if (p.kps > K) p.kps = K;
+    p.S = (K + p.kps - 1) / p.kps;
+    return p;
+  }
   if (M >= g_tune.tile_min_m && N % kMidN == 0 && N0 % kMidN == 0 && K % kFatK == 0) {
     p.kind = 4;
     p.mt = (M + kMidM - 1) / kMidM;
@@ -629,9 +653,10 @@ GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int 
     p.S = (K + p.kps - 1) / p.kps;
     return p;
   }
-  p.kind = 2;
+  const bool rows128 = g_tune.tall_max_m >= 128 && M > 64 && M <= 128 && NW == 8;
+  p.kind = rows128 ? 6 : 2;
   p.KC = (K % 256 == 0) ? 256 : 128;
-  p.mt = (M + 63) / 64;
+  p.mt = rows128 ? 1 : (M + 63) / 64;
   p.nt = N / BN;
   int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
   S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
@@ -653,7 +678,7 @@ int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const
   const bool al = aligned16(A) && aligned16(W0) && (W1 == nullptr || aligned16(W1));
   const GemmPlan p = plan_gemm(dtype, al, lda, M, N, N0, K, c_capacity);
   if (p.kind == 0 || static_cast<size_t>(p.S) * M * N > c_capacity) return 0;  // nothing launched
-  t_last_stream = p.kind == 2;
+  t_last_stream = p.kind == 2 || p.kind == 5 || p.kind == 6;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(W0);
   const bf16_t* w1 = static_cast<const bf16_t*>(W1);
@@ -676,6 +701,18 @@ int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const
     case 4:
       hipLaunchKernelGGL(k_gemm_mid, grid, dim3(256), 0, st, a, lda, rows, M, w0, w1, N0, N, K,
                          p.kps, c_part);
+      break;
+    case 6:
+      if (p.KC == 256)
+        launch_stream<8, 256, 0, 1, 8>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps, c_part, nullptr);
+      else
+        launch_stream<8, 128, 0, 1, 8>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps, c_part, nullptr);
+      break;
+    case 5:
+      if (g_tune.nw == 8)
+        launch_stream<8, 128, 0, 1, 16>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps, c_part, nullptr);
+      else
+        launch_stream<4, 128, 0, 1, 16>(grid, st, a, lda, rows, M, w0, w1, N0, N, K, p.kps, c_part, nullptr);
       break;
     default: {
 #define DLLMC_GS(NWv, KCv) \
@@ -720,7 +757,8 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
     }
   }
   if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % 16 == 0) || M > 128) return false;
-  const dim3 grid((m + BN - 1) / BN, (M + 63) / 64, 1);
+  const bool rows128 = g_tune.tall_max_m >= 128 && M > 64 && NW == 6 && KH == 2 && K % 256 == 0;
+  const dim3 grid((m + BN - 1) / BN, rows128 ? 1 : (M + 63) / 64, 1);
   t_last_stream = true;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
@@ -728,6 +766,10 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   bf16_t* uo = static_cast<bf16_t*>(u);
 #define DLLMC_GD(NWv, KCv, KHv) \
   launch_stream<NWv, KCv, 1, KHv>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
+  if (rows128) {
+    launch_stream<6, 128, 1, 2, 8>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo);
+    return true;
+  }
   switch (NW * 10 + KH) {
     case 62: if (KC == 256) DLLMC_GD(6, 256, 2); else DLLMC_GD(6, 128, 2); break;
     case 82: if (KC == 256) DLLMC_GD(8, 256, 2); else DLLMC_GD(8, 128, 2); break;

@@ -96,6 +96,8 @@ def test_select_rejects_bad_k():
     ("bf16", 20, 2432, 896, False),      # N = 19 * 128
     ("bf16", 40, 896, 2432, False),
     ("bf16", 17, 200, 72, True),         # falls back to the plain kernel
+    ("bf16", 100, 1024, 1024, True),     # streaming kernel, 128 rows per workgroup
+    ("bf16", 128, 512, 896, False),      # the same with phases of 128
     ("bf16", 256, 1024, 4096, True),     # 128 x 128 LDS-direct kernel, split contraction
     ("bf16", 300, 512, 896, True),       # tile kernel, ragged last row tile, K = 14 * 64
     ("bf16", 768, 2432, 1024, False),    # tile kernel, N = 19 * 128
@@ -120,6 +122,16 @@ def test_linear_fat_kernel(M, N, K):
         run_linear_case("bf16", M, N, K, True)
     finally:
         binding.set_gemm_tuning(fat_min_m=1024)
+
+
+@pytest.mark.parametrize("nw", [8, 4])
+@pytest.mark.parametrize("M,N,K", [(256, 1024, 4096), (200, 512, 896), (300, 2304, 1024), (512, 1024, 512)])
+def test_linear_streaming_kernel_with_256_rows_per_workgroup(M, N, K, nw):
+    binding.set_gemm_tuning(tall_max_m=512, nw=nw)
+    try:
+        run_linear_case("bf16", M, N, K, True)
+    finally:
+        binding.set_gemm_tuning(tall_max_m=128, nw=8)
 
 
 def run_linear_case(dtype, M, N, K, gather):
