@@ -653,10 +653,10 @@ GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int 
     p.S = (K + p.kps - 1) / p.kps;
     return p;
   }
-  const bool rows128 = g_tune.tall_max_m >= 128 && M > 64 && M <= 128 && NW == 8;
+  const bool rows128 = g_tune.tall_max_m >= 128 && M > 64 && NW == 8;
   p.kind = rows128 ? 6 : 2;
   p.KC = (K % 256 == 0) ? 256 : 128;
-  p.mt = rows128 ? 1 : (M + 63) / 64;
+  p.mt = rows128 ? (M + 127) / 128 : (M + 63) / 64;
   p.nt = N / BN;
   int S = g_tune.force_s > 0 ? g_tune.force_s : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
   S = S < 1 ? 1 : (S > s_cap ? s_cap : S);

@@ -98,6 +98,7 @@ def test_select_rejects_bad_k():
     ("bf16", 17, 200, 72, True),         # falls back to the plain kernel
     ("bf16", 100, 1024, 1024, True),     # streaming kernel, 128 rows per workgroup
     ("bf16", 128, 512, 896, False),      # the same with phases of 128
+    ("bf16", 150, 512, 1024, True),      # two such tiles, the second ragged
     ("bf16", 256, 1024, 4096, True),     # 128 x 128 LDS-direct kernel, split contraction
     ("bf16", 300, 512, 896, True),       # tile kernel, ragged last row tile, K = 14 * 64
     ("bf16", 768, 2432, 1024, False),    # tile kernel, N = 19 * 128
