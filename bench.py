@@ -306,15 +306,21 @@ def main():
         def mfma():
             fl[0] = binding.probe_mfma(4096, sink)
         t_mfma = timed(mfma)
+        fl32 = [0.0]
+
+        def mfma32():
+            fl32[0] = binding.probe_mfma(4096, sink, shape=1)
+        t_mfma32 = timed(mfma32)
         copy_gbs, read_gbs, mfma_tf = 2 * n_probe / t_copy / 1e9, n_probe / t_read / 1e9, fl[0] / t_mfma / 1e12
         result["achievable"] = {
             "copy_GBps": copy_gbs, "read_GBps": read_gbs, "mfma_bf16_TFLOPs": mfma_tf,
+            "mfma_bf16_32x32x16_TFLOPs": fl32[0] / t_mfma32 / 1e12,
             "note": "1 GiB plain copy (bytes in + bytes out), 1 GiB plain read, back-to-back "
-                    "16x16x32 bf16 MFMAs from registers; median of 10 launches",
+                    "16x16x32 / 32x32x16 bf16 MFMAs from registers; median of 10 launches",
         }
         rf = result.get("roofline")
         if rf:
-            ceil = read_gbs if rf["bound"] == "hbm" else mfma_tf
+            ceil = read_gbs if rf["bound"] == "hbm" else max(mfma_tf, fl32[0] / t_mfma32 / 1e12)
             rf["frac_of_measured_ceiling"] = rf["achieved"] / ceil if ceil > 0 else None
             rf["measured_ceiling"] = ceil
         del src, dst

@@ -294,13 +294,14 @@ int dllmc_op_attention(int32_t dtype, const void* q, int32_t B, int32_t Mq, cons
  *                     multiple of 16; moves bytes in and bytes out.
  *   dllmc_probe_read  reads src[0..bytes) once and writes nothing (sink: device, 4 bytes, is
  *                     only there to keep the loads alive).
- *   dllmc_probe_mfma  every wavefront of a grid that fills the chip issues iters * 8 independent
- *                     16x16x32 bf16 MFMAs from registers; *flops_out (host, may be NULL) = the
- *                     flops of the launch; sink: device float32 [256], 16-byte aligned,
- *                     overwritten. */
+ *   dllmc_probe_mfma  every wavefront of a grid that fills the chip issues, from registers,
+ *                     iters * 8 independent 16x16x32 bf16 MFMAs (shape 0) or iters * 4
+ *                     independent 32x32x16 ones (shape 1; the same flops); *flops_out (host,
+ *                     may be NULL) = the flops of the launch; sink: device float32 [256],
+ *                     16-byte aligned, overwritten. */
 int dllmc_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
 int dllmc_probe_read(const void* src, size_t bytes, void* sink, void* hip_stream);
-int dllmc_probe_mfma(int32_t iters, float* sink, double* flops_out, void* hip_stream);
+int dllmc_probe_mfma(int32_t iters, int32_t shape, float* sink, double* flops_out, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -142,7 +142,7 @@ def lib() -> C.CDLL:
         L.dllmc_probe_read.restype = C.c_int
         L.dllmc_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.dllmc_probe_mfma.restype = C.c_int
-        L.dllmc_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+        L.dllmc_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         _lib = L
     return _lib
 
@@ -414,9 +414,9 @@ def probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
                                   _stream_handle()), "dllmc_probe_read")
 
 
-def probe_mfma(iters: int, sink: torch.Tensor) -> float:
-    """Enqueues the MFMA loop; returns the flops of the launch."""
+def probe_mfma(iters: int, sink: torch.Tensor, shape: int = 0) -> float:
+    """Enqueues the MFMA loop (shape 0: 16x16x32, 1: 32x32x16); returns the flops of the launch."""
     f = C.c_double(0.0)
-    _check(lib().dllmc_probe_mfma(iters, sink.data_ptr(), C.byref(f), _stream_handle()),
+    _check(lib().dllmc_probe_mfma(iters, shape, sink.data_ptr(), C.byref(f), _stream_handle()),
            "dllmc_probe_mfma")
     return f.value

@@ -207,7 +207,7 @@ void launch_apply_tokens(int* tokens, int B, int n, int L_p, const int* chosen, 
 // returns the flops its launch performs
 void launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 void launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
-double launch_probe_mfma(int iters, float* sink, hipStream_t st);
+double launch_probe_mfma(int iters, int shape, float* sink, hipStream_t st);
 
 // sel[r][j] = j for r < rows, j < L_r
 void launch_fill_sel_identity(int* sel, int rows, int L_r, hipStream_t st);

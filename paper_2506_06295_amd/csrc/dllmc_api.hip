@@ -837,11 +837,12 @@ int dllmc_probe_read(const void* src, size_t bytes, void* sink, void* hip_stream
   return DLLMC_OK;
 }
 
-int dllmc_probe_mfma(int32_t iters, float* sink, double* flops_out, void* hip_stream) {
-  if (iters < 1 || iters > (1 << 24) || !sink || (reinterpret_cast<uintptr_t>(sink) & 15u))
+int dllmc_probe_mfma(int32_t iters, int32_t shape, float* sink, double* flops_out, void* hip_stream) {
+  if (iters < 1 || iters > (1 << 24) || shape < 0 || shape > 1 || !sink ||
+      (reinterpret_cast<uintptr_t>(sink) & 15u))
     return DLLMC_EINVAL;
   (void)hipGetLastError();
-  const double f = launch_probe_mfma(iters, sink, static_cast<hipStream_t>(hip_stream));
+  const double f = launch_probe_mfma(iters, shape, sink, static_cast<hipStream_t>(hip_stream));
   if (flops_out) *flops_out = f;
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;

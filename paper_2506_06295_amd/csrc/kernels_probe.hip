@@ -69,6 +69,35 @@ __global__ __launch_bounds__(kThreads) void k_probe_mfma(int iters, float* __res
     *reinterpret_cast<f32x4*>(sink + threadIdx.x * 4) = s;
 }
 
+// the same with four independent 32x32x16 bf16 MFMAs per trip (the same flops per trip)
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+__global__ __launch_bounds__(kThreads) void k_probe_mfma32(int iters, float* __restrict__ sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = static_cast<__bf16>(static_cast<float>((threadIdx.x + i) & 7) * 0.125f);
+    b[i] = static_cast<__bf16>(static_cast<float>((threadIdx.x * 3 + i) & 7) * 0.125f);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+  for (int t = 0; t < iters; ++t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  f32x16 s = acc[0];
+#pragma unroll
+  for (int j = 1; j < 4; ++j) s += acc[j];
+  if (blockIdx.x == 0 && threadIdx.x < kWave) {
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t += s[e];
+    sink[threadIdx.x] = t;
+  }
+}
+
 int probe_grid() {
   int dev = 0, cus = 256;
   if (hipGetDevice(&dev) == hipSuccess)
@@ -90,9 +119,12 @@ void launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_
                      static_cast<const uint4*>(src), bytes / 16, sink);
 }
 
-double launch_probe_mfma(int iters, float* sink, hipStream_t st) {
+double launch_probe_mfma(int iters, int shape, float* sink, hipStream_t st) {
   const int grid = probe_grid();
-  hipLaunchKernelGGL(k_probe_mfma, dim3(grid), dim3(kThreads), 0, st, iters, sink);
+  if (shape == 1)
+    hipLaunchKernelGGL(k_probe_mfma32, dim3(grid), dim3(kThreads), 0, st, iters, sink);
+  else
+    hipLaunchKernelGGL(k_probe_mfma, dim3(grid), dim3(kThreads), 0, st, iters, sink);
   // wavefronts x trips x 8 MFMAs x (16 * 16 * 32 multiply-adds, two flops each)
   return static_cast<double>(grid) * (kThreads / kWave) * iters * 8.0 * (2.0 * 16 * 16 * 32);
 }

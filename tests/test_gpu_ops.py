@@ -255,3 +255,27 @@ def test_probe_mfma_result_follows_the_instruction_layout():
     assert np.array_equal(sink.cpu().numpy().astype(np.float64), want)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     assert flops == cus * 8 * 4 * iters * 8 * 2 * 16 * 16 * 32
+
+
+def test_probe_mfma_32x32x16_result_follows_the_instruction_layout():
+    """Shape 1 of the MFMA loop: four accumulators x iters x (A @ B) with 32 x 16 and 16 x 32
+    operands (A: row = lane % 32, k = 8 * (lane / 32) + i; B alike with the column); a lane
+    writes the sum of its 16 results: column lane % 32, rows 8 * (e / 4) + 4 * (lane / 32) + e % 4."""
+    iters = 2
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    flops = binding.probe_mfma(iters, sink, shape=1)
+    torch.cuda.synchronize()
+    A = np.zeros((32, 16))
+    Bm = np.zeros((16, 32))
+    for lane in range(64):
+        for i in range(8):
+            A[lane % 32, 8 * (lane // 32) + i] = ((lane + i) & 7) / 8.0
+            Bm[8 * (lane // 32) + i, lane % 32] = ((3 * lane + i) & 7) / 8.0
+    Cm = 4 * iters * (A @ Bm)
+    want = np.array([sum(Cm[8 * (e // 4) + 4 * (lane // 32) + e % 4, lane % 32] for e in range(16))
+                     for lane in range(64)])
+    assert np.array_equal(sink[:64].cpu().numpy().astype(np.float64), want)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert flops == cus * 8 * 4 * iters * 4 * 2 * 32 * 32 * 16
+    with pytest.raises(binding.DllmcError):
+        binding.probe_mfma(1, sink, shape=2)
