@@ -784,6 +784,7 @@ int dllmc_gen_read(dllmc_gen* g, int32_t* x0, float* conf, int32_t* chosen, void
 }
 
 int dllmc_gen_destroy(dllmc_gen* g) {
+  if (!g) return DLLMC_EINVAL;
   delete g;
   return DLLMC_OK;
 }

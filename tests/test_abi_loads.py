@@ -49,3 +49,16 @@ def test_host_only_calls_work_without_a_gpu():
     assert L.dllmc_create(ctypes.byref(h), ctypes.byref(m), None, 512, 256, 0.25, 50, 7, None, 0, None) == -1
     assert L.dllmc_step(None, None, 0, None, None, None) == -1
     assert L.dllmc_destroy(None) == -1
+
+
+def test_argument_checks_of_the_later_entry_points_need_no_gpu():
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.skip("libdllmc.so not built in this tree")
+    L = binding.lib()
+    assert L.dllmc_set_layer_rho(None, None, 0) == -1
+    assert L.dllmc_layer_num_selected(None, 0) == -1
+    assert L.dllmc_set_policy(None, 0, 0, 0, 0, 0) == -1
+    assert L.dllmc_probe_copy(None, None, 1024, None) == -1
+    assert L.dllmc_probe_read(None, 1024, None, None) == -1
+    assert L.dllmc_probe_mfma(0, 0, None, None, None) == -1
+    assert L.dllmc_gen_destroy(None) == -1
