@@ -404,18 +404,31 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // Two ways through a step.  One workgroup per CU (the 256 x 256 tile): a single barrier,
+  // behind which everybody's loads of step kt have landed AND everybody has finished the
+  // fragment reads of step kt-1, so the loads of step kt+1 are issued right after it into the
+  // other stage.  Two workgroups per CU (128 x 128): the loads of step kt+1 go out before the
+  // wait for step kt (a longer window for the shorter steps) and a second barrier at the end of
+  // the step protects the stage they overwrite.
+  constexpr bool ONE_BARRIER = NWV == 8;
   DLLMC_LDS_ISSUE(0, 0)
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < nkt;
-    if (more) {
-      DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
-      wait_vmcnt<LA + LB>();  // this wavefront's loads of step kt have landed
+    if (ONE_BARRIER) {
+      wait_vmcnt<0>();  // this wavefront's loads of step kt have landed
+      __builtin_amdgcn_s_barrier();
+      if (more) DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
     } else {
-      wait_vmcnt<0>();
+      if (more) {
+        DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
+        wait_vmcnt<LA + LB>();  // this wavefront's loads of step kt have landed
+      } else {
+        wait_vmcnt<0>();
+      }
+      // bare barrier (no memory fence: a fence would wait for the loads of step kt+1 as well)
+      __builtin_amdgcn_s_barrier();  // ... and everybody else's
     }
-    // bare barrier (no memory fence: a fence would wait for the loads of step kt+1 as well)
-    __builtin_amdgcn_s_barrier();  // ... and everybody else's
     const uint4* la = &lds[cur][0];
     const uint4* lb = &lds[cur][BM * 8];
 #pragma unroll
@@ -440,9 +453,9 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
-    // all LDS reads of this stage are complete (their results fed the MFMAs above) before the
-    // loads issued in the next iteration overwrite it
-    __builtin_amdgcn_s_barrier();
+    // two-barrier scheme: all LDS reads of this stage are complete (their results fed the MFMAs
+    // above) before the loads issued at the top of the next iteration overwrite it
+    if (!ONE_BARRIER) __builtin_amdgcn_s_barrier();
   }
 #undef DLLMC_LDS_ISSUE
 
