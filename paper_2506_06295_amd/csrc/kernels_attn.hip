@@ -75,20 +75,131 @@ constexpr int kQT = 64;        // queries per workgroup: four wavefronts x 16
 constexpr int kPreload = 3;    // key ranges of up to this many 32-key blocks are fetched whole
 constexpr int kMaxKeySplit = 16;
 
+// One 32-key block for a wavefront's 16 queries: scores S^T = K Q^T, running softmax (base 2),
+// O^T += V^T P^T.  kf: K fragments (lane: key sb*16 + ln, dims 32c + 8lg .. +8); qf: Q fragments
+// (lane: query ln, same dims); vt: the block's V tile transposed, [dim][VS keys] (SWZ: with the
+// key pairs of a row permuted, see k_attn_mfma).
+template <int VS, bool SWZ>
+__device__ __forceinline__ void attn_block(const bf16x8 (&kf)[2][4], const bf16x8 (&qf)[4],
+                                           const bf16_t* vt, int key0, int n, int ln, int lg,
+                                           float sl2e, float& m_run, float& l_run,
+                                           f32x4 (&o_acc)[8]) {
+  f32x4 st[2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sb][c], qf[c], acc, 0, 0, 0);
+    st[sb] = acc;
+  }
+  // lane holds keys key0 + sb*16 + 4*lg + i of query ln
+  float p[8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int key = key0 + sb * 16 + 4 * lg + i;
+      const float v = key < n ? st[sb][i] * sl2e : -INFINITY;
+      p[sb * 4 + i] = v;
+      mx = fmaxf(mx, v);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(m_run, mx);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;
+  const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
+  // probabilities as a bf16 pair (high part + remainder): the second product then carries
+  // ~16 bits of each probability instead of 8
+  float psum = 0.f;
+  bf16x8 pf, pl;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    const float e = exp2f(p[t] - m_use);
+    psum += e;
+    const __bf16 hi = static_cast<__bf16>(e);
+    pf[t] = hi;
+    pl[t] = static_cast<__bf16>(e - static_cast<float>(hi));
+  }
+  l_run = l_run * alpha + psum;
+  m_run = m_new;
+#pragma unroll
+  for (int db = 0; db < 8; ++db) {
+    o_acc[db][0] *= alpha;
+    o_acc[db][1] *= alpha;
+    o_acc[db][2] *= alpha;
+    o_acc[db][3] *= alpha;
+  }
+  // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
+#pragma unroll
+  for (int db = 0; db < 8; ++db) {
+    // SWZ: key pair p of the rows of dim block db sits at pair position p ^ 2*db
+    const bf16_t* vrow = vt + (db * 16 + ln) * VS;
+    const uint2 lo = *reinterpret_cast<const uint2*>(vrow + (SWZ ? (4 * lg) ^ (4 * db) : 4 * lg));
+    const uint2 hi =
+        *reinterpret_cast<const uint2*>(vrow + (SWZ ? (16 + 4 * lg) ^ (4 * db) : 16 + 4 * lg));
+    const uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+    o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[db], 0, 0, 0);
+    o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o_acc[db], 0, 0, 0);
+  }
+}
+
+// End of a key range for query iq (lane's column of O^T): with KS == 1 the normalised output row,
+// otherwise the un-normalised partial (O, m, l) of range ks for k_attn_merge.
+__device__ __forceinline__ void attn_finish(const f32x4 (&o_acc)[8], float m_run, float l_run, int iq,
+                                            int Mq, int b, int a, int ks, int KS, int H_q, int lg,
+                                            bf16_t* __restrict__ out, float* __restrict__ part) {
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (iq >= Mq) return;
+  const int d_q = H_q * kDH;
+  if (KS == 1) {
+    const float inv_l = 1.0f / l_run;
+    bf16_t* o = out + (static_cast<size_t>(b) * Mq + iq) * d_q + a * kDH;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      uint2 t;
+      t.x = static_cast<uint32_t>(f32_to_bf16(o_acc[db][0] * inv_l)) |
+            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][1] * inv_l)) << 16);
+      t.y = static_cast<uint32_t>(f32_to_bf16(o_acc[db][2] * inv_l)) |
+            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][3] * inv_l)) << 16);
+      *reinterpret_cast<uint2*>(o + db * 16 + 4 * lg) = t;
+    }
+  } else {
+    // part[((b*Mq + iq)*H_q + a)*KS + ks][kDH + 2]
+    float* w = part + ((static_cast<size_t>(b) * Mq + iq) * H_q + a) * KS * (kDH + 2) +
+               static_cast<size_t>(ks) * (kDH + 2);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      *reinterpret_cast<float4*>(w + db * 16 + 4 * lg) =
+          make_float4(o_acc[db][0], o_acc[db][1], o_acc[db][2], o_acc[db][3]);
+    if (lg == 0) {
+      w[kDH] = m_run;
+      w[kDH + 1] = l_run;
+    }
+  }
+}
+
 // Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; blockIdx.z
-// enumerates (sequence, key range).  All four wavefronts walk the same 32-key blocks, so a V
-// tile is transposed through LDS once per workgroup.  K fragments and the next V tile are
-// fetched one block ahead.  With KS == 1 the normalised output is written; otherwise the
-// un-normalised partial (O, m, l) of this key range goes to `part` for k_attn_merge.
-// PRELOAD: every key range is at most kPreload blocks long (the launcher guarantees it) and is
-// fetched whole before its first use; the other instantiation walks its range block by block
-// and, without the preloaded fragments, keeps its accumulators in ordinary registers.
-template <bool PRELOAD>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_attn_mfma(const bf16_t* __restrict__ q, int Mq,
-                                                   const bf16_t* __restrict__ kc,
-                                                   const bf16_t* __restrict__ vc, int n, int H_q,
-                                                   int H_kv, int KS, bf16_t* __restrict__ out,
-                                                   float* __restrict__ part) {
+// enumerates (sequence, key range).  All four wavefronts use the same 32-key blocks, so a V
+// tile is transposed through LDS once per workgroup.  With KS == 1 the normalised output is
+// written; otherwise the un-normalised partial (O, m, l) of this key range goes to `part` for
+// k_attn_merge.
+// k_attn_mfma: key ranges of at most kPreload blocks (the launcher guarantees it: split keys of
+// an adaptive step).  Every K fragment and V tile of the range is requested before the first
+// one is used, so the range costs one trip to memory instead of one per block.
+// V transposition: thread = (key pair kp, 16-byte chunk ch) loads the chunk of keys 2kp and 2kp+1
+// (16 consecutive lanes read one key's 256 bytes) and writes, per dim, one 32-bit word holding
+// both keys at pair position kp ^ (ch & 14) of the dim's row: the 16 lanes of a key pair then
+// hit 16 different banks (lanes along the dims with 16-bit stores spend 7 of 8 LDS cycles on
+// bank conflicts), and ch & 14 = 2 * (dim / 16) is the same for all rows of a dim block, so the
+// reader undoes it with a constant.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_attn_mfma(
+    const bf16_t* __restrict__ q, int Mq, const bf16_t* __restrict__ kc,
+    const bf16_t* __restrict__ vc, int n, int H_q, int H_kv, int KS, bf16_t* __restrict__ out,
+    float* __restrict__ part) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kPreload][kDH * kVtStride];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
@@ -120,178 +231,173 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
   const int per = (nblk + KS - 1) / KS;
   const int blk0 = ks * per;
   const int blk1 = min(nblk, blk0 + per);
-
-  // staging assignment: 32 keys x 16 chunks of 8 dims = 512 chunks, two per thread
-  const int skey = threadIdx.x / 16, sc = threadIdx.x % 16;  // keys skey and skey + 16
-  auto load_v = [&](int blk, uint4 (&raw)[2]) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      int kr = blk * 32 + skey + 16 * h;
-      if (kr >= n) kr = n - 1;  // masked below; any finite value will do
-      raw[h] = *reinterpret_cast<const uint4*>(V + static_cast<size_t>(kr) * d_kv + sc * 8);
-    }
-  };
-  auto store_v = [&](bf16_t* dst, const uint4 (&raw)[2]) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const uint32_t w[4] = {raw[h].x, raw[h].y, raw[h].z, raw[h].w};
-      const int key = skey + 16 * h;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        dst[(sc * 8 + 2 * j) * kVtStride + key] = static_cast<bf16_t>(w[j] & 0xffffu);
-        dst[(sc * 8 + 2 * j + 1) * kVtStride + key] = static_cast<bf16_t>(w[j] >> 16);
-      }
-    }
-  };
-  auto load_k = [&](int blk, bf16x8 (&kf)[2][4]) {
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      int kr = blk * 32 + sb * 16 + ln;
-      if (kr >= n) kr = n - 1;
-      const bf16_t* kp = K + static_cast<size_t>(kr) * d_kv + lg * 8;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) kf[sb][c] = *reinterpret_cast<const bf16x8*>(kp + c * 32);
-    }
-  };
-
-  // One 32-key block: scores S^T = K Q^T, running softmax, O^T += V^T P^T.
-  auto process = [&](const bf16x8 (&kf)[2][4], const bf16_t* vt, int key0) {
-    // scores of the two 16-key halves: S^T[key][query]
-    f32x4 st[2];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[sb][c], qf[c], acc, 0, 0, 0);
-      st[sb] = acc;
-    }
-    // lane holds keys key0 + sb*16 + 4*lg + i of query ln
-    float p[8];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = key0 + sb * 16 + 4 * lg + i;
-        const float v = key < n ? st[sb][i] * sl2e : -INFINITY;
-        p[sb * 4 + i] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
-    // probabilities as a bf16 pair (high part + remainder): the second product then carries
-    // ~16 bits of each probability instead of 8
-    float psum = 0.f;
-    bf16x8 pf, pl;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const float e = exp2f(p[t] - m_use);
-      psum += e;
-      const __bf16 hi = static_cast<__bf16>(e);
-      pf[t] = hi;
-      pl[t] = static_cast<__bf16>(e - static_cast<float>(hi));
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      o_acc[db][0] *= alpha;
-      o_acc[db][1] *= alpha;
-      o_acc[db][2] *= alpha;
-      o_acc[db][3] *= alpha;
-    }
-    // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
-#pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      const bf16_t* vr = vt + (db * 16 + ln) * kVtStride + 4 * lg;
-      const uint2 lo = *reinterpret_cast<const uint2*>(vr);
-      const uint2 hi = *reinterpret_cast<const uint2*>(vr + 16);
-      const uint4 both = make_uint4(lo.x, lo.y, hi.x, hi.y);
-      const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o_acc[db], 0, 0, 0);
-      o_acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl, o_acc[db], 0, 0, 0);
-    }
-  };
-
   const int nb = blk1 - blk0;
-  if (PRELOAD && nb > 0) {
-    // Short key range (split keys of an adaptive step): every K fragment and V tile of the
-    // range is requested before the first one is used, so the range costs one trip to memory
-    // instead of one per block.
+
+  if (nb > 0) {
+    const int kp = threadIdx.x / 16, ch = threadIdx.x % 16;
     bf16x8 kall[kPreload][2][4];
     uint4 vall[kPreload][2];
 #pragma unroll
     for (int j = 0; j < kPreload; ++j) {
       const int blk = min(blk0 + j, blk1 - 1);  // blocks past the range repeat the last one, unused
-      load_k(blk, kall[j]);
-      load_v(blk, vall[j]);
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        int kr = blk * 32 + sb * 16 + ln;
+        if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
+        const bf16_t* kptr = K + static_cast<size_t>(kr) * d_kv + lg * 8;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) kall[j][sb][c] = *reinterpret_cast<const bf16x8*>(kptr + c * 32);
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        int kr = blk * 32 + 2 * kp + h;
+        if (kr >= n) kr = n - 1;
+        vall[j][h] = *reinterpret_cast<const uint4*>(V + static_cast<size_t>(kr) * d_kv + ch * 8);
+      }
     }
 #pragma unroll
-    for (int j = 0; j < kPreload; ++j) store_v(Vt[j], vall[j]);
+    for (int j = 0; j < kPreload; ++j) {
+      uint32_t* vt32 = reinterpret_cast<uint32_t*>(Vt[j]);
+      const uint32_t e0[4] = {vall[j][0].x, vall[j][0].y, vall[j][0].z, vall[j][0].w};
+      const uint32_t e1[4] = {vall[j][1].x, vall[j][1].y, vall[j][1].z, vall[j][1].w};
+      const int pos = kp ^ (ch & 14);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int dim = ch * 8 + 2 * t;
+        vt32[(dim * kVtStride) / 2 + pos] = (e0[t] & 0xffffu) | (e1[t] << 16);
+        vt32[((dim + 1) * kVtStride) / 2 + pos] = (e0[t] >> 16) | (e1[t] & 0xffff0000u);
+      }
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kPreload; ++j)
-      if (j < nb) process(kall[j], Vt[j], (blk0 + j) * 32);
-  } else if (!PRELOAD && nb > 0) {
-    uint4 vraw[2];
-    bf16x8 kf[2][4];
-    load_v(blk0, vraw);
-    load_k(blk0, kf);
-    store_v(Vt[0], vraw);
-    __syncthreads();
-    for (int blk = blk0; blk < blk1; ++blk) {
-      const int cur = (blk - blk0) & 1;
-      const bool more = blk + 1 < blk1;
-      bf16x8 kn[2][4];
-      if (more) {
-        load_v(blk + 1, vraw);
-        load_k(blk + 1, kn);
-      }
-      process(kf, Vt[cur], blk * 32);
-      if (more) {
-        store_v(Vt[cur ^ 1], vraw);
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-          for (int c = 0; c < 4; ++c) kf[sb][c] = kn[sb][c];
-      }
-      __syncthreads();
-    }
+      if (j < nb)
+        attn_block<kVtStride, true>(kall[j], qf, Vt[j], (blk0 + j) * 32, n, ln, lg, sl2e, m_run, l_run,
+                                    o_acc);
   }
+  attn_finish(o_acc, m_run, l_run, i0 + ln, Mq, b, a, ks, KS, H_q, lg, out, part);
+}
 
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
-  const int iq = i0 + ln;
-  if (iq >= Mq) return;
-  if (KS == 1) {
-    const float inv_l = 1.0f / l_run;
-    bf16_t* o = out + (static_cast<size_t>(b) * Mq + iq) * d_q + a * kDH;
+// ---- long key ranges -----------------------------------------------------------------
+// k_attn_walk: the same tiling and arithmetic as k_attn_mfma for key ranges of more than kPreload
+// blocks (many queries, or long sequences).  A block-by-block walk that fetches one block ahead
+// into registers is bound by the memory latency of every block; here the K and V tiles of a
+// block go from global memory straight into LDS (global_load_lds: no registers held while they
+// are in flight), kWalkStages - 1 blocks ahead.  K fragments are then read from LDS (slot =
+// chunk ^ (key % 16), so the 16 keys of a fragment read hit 16 different slots); the V tile is
+// read back row-wise and written transposed into Vt as in the other kernel.
+constexpr int kWalkStages = 4;
+constexpr int kVtStrideW = 36;  // 32 keys + 4 pad: rows of 8 dims apart start 16 banks apart
+
+__global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q, int Mq,
+                                                   const bf16_t* __restrict__ kc,
+                                                   const bf16_t* __restrict__ vc, int n, int H_q,
+                                                   int H_kv, int KS, bf16_t* __restrict__ out,
+                                                   float* __restrict__ part) {
+  // [stage][K tile, V tile][32 keys][16 slots of 16 bytes]
+  __shared__ __attribute__((aligned(1024))) uint4 tiles[kWalkStages][2][32 * 16];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[kDH * kVtStrideW];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int a = blockIdx.y;
+  const int b = blockIdx.z / KS, ks = blockIdx.z % KS;
+  const int d_q = H_q * kDH, d_kv = H_kv * kDH;
+  const int kv = a / (H_q / H_kv);
+  const int i0 = blockIdx.x * kQT + wave * 16;
+
+  const bf16_t* K = kc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
+  const bf16_t* V = vc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
+
+  int qi = i0 + ln;
+  if (qi >= Mq) qi = Mq - 1;  // padded queries compute a duplicate that is never stored
+  const bf16_t* qr = q + (static_cast<size_t>(b) * Mq + qi) * d_q + a * kDH + lg * 8;
+  bf16x8 qf[4];
 #pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      uint2 t;
-      t.x = static_cast<uint32_t>(f32_to_bf16(o_acc[db][0] * inv_l)) |
-            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][1] * inv_l)) << 16);
-      t.y = static_cast<uint32_t>(f32_to_bf16(o_acc[db][2] * inv_l)) |
-            (static_cast<uint32_t>(f32_to_bf16(o_acc[db][3] * inv_l)) << 16);
-      *reinterpret_cast<uint2*>(o + db * 16 + 4 * lg) = t;
-    }
-  } else {
-    // part[((b*Mq + iq)*H_q + a)*KS + ks][kDH + 2]
-    float* w = part + ((static_cast<size_t>(b) * Mq + iq) * H_q + a) * KS * (kDH + 2) +
-               static_cast<size_t>(ks) * (kDH + 2);
+  for (int c = 0; c < 4; ++c) qf[c] = *reinterpret_cast<const bf16x8*>(qr + c * 32);
+
+  const float sl2e = 1.4426950408889634f / sqrtf(static_cast<float>(kDH));
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 o_acc[8];
 #pragma unroll
-    for (int db = 0; db < 8; ++db)
-      *reinterpret_cast<float4*>(w + db * 16 + 4 * lg) =
-          make_float4(o_acc[db][0], o_acc[db][1], o_acc[db][2], o_acc[db][3]);
-    if (lg == 0) {
-      w[kDH] = m_run;
-      w[kDH + 1] = l_run;
+  for (int db = 0; db < 8; ++db) o_acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nblk = (n + 31) / 32;
+  const int per = (nblk + KS - 1) / KS;
+  const int blk0 = ks * per;
+  const int blk1 = min(nblk, blk0 + per);
+  const int nb = blk1 - blk0;
+
+  if (nb > 0) {
+    // loader: a tile is 8 wavefront instructions of 4 keys x 256 bytes; wavefront w issues
+    // instructions 2w and 2w+1 of the K and of the V tile.  Lane l: key 4q + l/16, slot l%16.
+    // LDS slot l%16 of a key's row holds chunk slot ^ (key % 16) of K (the 16 keys of a
+    // fragment read hit 16 slots) and chunk slot ^ (key/2 % 16) of V (so do the 16 key pairs
+    // of the transposition)
+    int lkey[2], kchunk[2], vchunk[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      lkey[j] = 4 * (2 * wave + j) + lane / 16;
+      kchunk[j] = (lane % 16) ^ (lkey[j] % 16);
+      vchunk[j] = (lane % 16) ^ ((lkey[j] >> 1) % 16);
     }
+    auto issue = [&](int blk, int stage) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        int kr = blk * 32 + lkey[j];
+        if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
+        const size_t row = static_cast<size_t>(kr) * d_kv;
+        __builtin_amdgcn_global_load_lds(K + row + kchunk[j] * 8, &tiles[stage][0][(2 * wave + j) * 64],
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds(V + row + vchunk[j] * 8, &tiles[stage][1][(2 * wave + j) * 64],
+                                         16, 0, 0);
+      }
+    };
+    // blocks past the range repeat the last one (never used): the number of loads in flight
+    // stays the same in every iteration
+#pragma unroll
+    for (int s = 0; s < kWalkStages - 1; ++s) issue(min(blk0 + s, blk1 - 1), s);
+
+    // V transposition: thread = (key pair kp, 16-byte chunk vch); it reads the chunk of keys 2kp
+    // and 2kp+1 and writes, per dim, one 32-bit word holding both keys.  Consecutive lanes write
+    // consecutive words of a Vt row and the four chunks of a wavefront sit 16 banks apart (row
+    // stride 36 elements), so the writes are free of bank conflicts; 16-bit stores with lanes
+    // along the dims spend 7 of 8 LDS cycles on conflicts.
+    const int kp = threadIdx.x % 16, vch = threadIdx.x / 16;
+    uint32_t* vt32 = reinterpret_cast<uint32_t*>(Vt);
+    for (int i = 0; i < nb; ++i) {
+      const int stage = i % kWalkStages;
+      // 4 loads per block and wavefront, kWalkStages - 1 blocks in flight: the oldest has landed
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * (kWalkStages - 2)) & 15) |
+                                 (((4 * (kWalkStages - 2)) >> 4) << 14));
+      // everybody's loads of block i have landed, and everybody is done with block i - 1: its
+      // stage and Vt may be overwritten
+      __builtin_amdgcn_s_barrier();
+      issue(min(blk0 + i + kWalkStages - 1, blk1 - 1), (i + kWalkStages - 1) % kWalkStages);
+      {
+        const uint4 r0 = tiles[stage][1][(2 * kp) * 16 + (vch ^ kp)];
+        const uint4 r1 = tiles[stage][1][(2 * kp + 1) * 16 + (vch ^ kp)];
+        const uint32_t e0[4] = {r0.x, r0.y, r0.z, r0.w}, e1[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int dim = vch * 8 + 2 * j;
+          vt32[(dim * kVtStrideW) / 2 + kp] = (e0[j] & 0xffffu) | (e1[j] << 16);
+          vt32[((dim + 1) * kVtStrideW) / 2 + kp] = (e0[j] >> 16) | (e1[j] & 0xffff0000u);
+        }
+      }
+      // K fragments of this wavefront: key sb*16 + ln, dims 32c + 8lg .. +8 = chunk 4c + lg
+      bf16x8 kf[2][4];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          kf[sb][c] = __builtin_bit_cast(bf16x8, tiles[stage][0][(sb * 16 + ln) * 16 + ((4 * c + lg) ^ ln)]);
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // LDS writes of Vt done (lgkmcnt 0); global loads stay in flight
+      __builtin_amdgcn_s_barrier();
+      attn_block<kVtStrideW, false>(kf, qf, Vt, (blk0 + i) * 32, n, ln, lg, sl2e, m_run, l_run, o_acc);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // the repeated loads past the range, before the LDS goes away
   }
+  attn_finish(o_acc, m_run, l_run, i0 + ln, Mq, b, a, ks, KS, H_q, lg, out, part);
 }
 
 // out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.
@@ -361,11 +467,11 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
       if (KS > (nblk + 2) / 3) KS = (nblk + 2) / 3;
     }
     if ((nblk + KS - 1) / KS <= kPreload)
-      hipLaunchKernelGGL(k_attn_mfma<true>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
-                         H_q, H_kv, KS, oo, scratch);
+      hipLaunchKernelGGL(k_attn_mfma, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
+                         H_kv, KS, oo, scratch);
     else
-      hipLaunchKernelGGL(k_attn_mfma<false>, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n,
-                         H_q, H_kv, KS, oo, scratch);
+      hipLaunchKernelGGL(k_attn_walk, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
+                         H_kv, KS, oo, scratch);
     if (KS > 8)
       hipLaunchKernelGGL(k_attn_merge<kMaxKeySplit>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS,
                          H_q, oo);
