@@ -123,7 +123,10 @@ __global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, in
 // is written to the other LDS buffer at the end of the phase (one barrier per phase).  The
 // weight stream is prefetched one whole phase ahead and runs across phase boundaries.
 // Lane (n = lane%16, g = lane/16) holds, for MFMA step c of a 128-wide step, the eight
-// weights W[col n][k0 + 32c + 8g ..+8]; the A operand is read from LDS at the same offsets.
+// weights W[col n][k0 + 32c + 8g ..+8]; the A operand is read from LDS at the same offsets
+// (the 16-byte chunks of an LDS row are XOR-permuted in groups of 16 by row % 16, which keeps
+// the fragment reads free of bank conflicts; with a padded row stride, or a permutation by
+// row % 8, half of the LDS cycles of the reads were conflicts).
 //   DUAL = 0: columns [0,N0) come from W0, [N0,N) from W1; float32 partial sums are stored
 //             to slice blockIdx.z of C.
 //   DUAL = 1: every lane streams row n of W0 (gate) and row n of W1 (up) and the epilogue
@@ -145,7 +148,8 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, int N0, int N, int K,
     int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
-  constexpr int LS = KC + 8;                      // LDS row stride: rows start 4 banks apart
+  constexpr int LS = KC;                          // LDS row stride; chunk q of row r sits in slot
+                                                  // q ^ (r % 16) of its group of 16 (no padding)
   constexpr int CPR = KC / 8;                     // 16-byte chunks per activation row and phase
   constexpr int R = 16 * RB;                      // activation rows per workgroup
   constexpr int TOT = KH * R * CPR;               // chunks of the workgroup's activation tiles
@@ -192,13 +196,18 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     aval[j] = ain[j] && m < M;
     const int row = aval[j] ? (rows ? rows[m] : m) : 0;
     asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + h * hlen + c * 8;
-    adst[j] = h * R * LS + r * LS + c * 8;
+    adst[j] = h * R * LS + r * LS + (c ^ (r % 16)) * 8;
   }
   f32x4 acc[NB][RB];
 #pragma unroll
   for (int b = 0; b < NB; ++b)
 #pragma unroll
     for (int i = 0; i < RB; ++i) acc[b][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // element offsets, within a 128-wide step, of this lane's four fragment chunks 4c + lg after
+  // the slot permutation of its row (rows mb*16 + ln share row % 16 = ln)
+  int fo[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) fo[c] = ((4 * c + lg) ^ ln) * 8;
 
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
         if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + (ph + 1) * KC);
       }
     }
-    const bf16_t* ap = &As[ph & 1][kh][ln * LS + lg * 8];
+    const bf16_t* ap = &As[ph & 1][kh][ln * LS];
 #pragma unroll
     for (int t = 0; t < NS; ++t) {
       uint4 bc[NB][4];
@@ -249,7 +258,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
         for (int mb = 0; mb < RB; ++mb) {
           const bf16x8 af =
-              *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + t * 128 + c * 32);
+              *reinterpret_cast<const bf16x8*>(ap + mb * 16 * LS + t * 128 + fo[c]);
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
