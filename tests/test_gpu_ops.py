@@ -198,6 +198,8 @@ def test_vverify_scores_and_cache_overwrite(dtype, rows, d, d_kv):
     ("bf16", 2, 20, 176, 8, 8, 128),     # ragged queries and keys
     ("bf16", 1, 51, 333, 7, 1, 128),     # grouped KV heads
     ("bf16", 3, 200, 200, 28, 4, 128),   # many queries: query-tiled variant
+    ("bf16", 1, 40, 2500, 2, 2, 128),    # long key ranges: 16 ranges of 5 blocks, the last one shorter
+    ("bf16", 2, 70, 1100, 8, 2, 128),    # the same with grouped KV heads and two query tiles
     ("bf16", 1, 7, 5, 2, 2, 128),        # fewer keys than one block
     ("bf16", 1, 9, 70, 2, 1, 64),        # head width without an MFMA kernel
 ])
