@@ -96,41 +96,57 @@ __device__ __forceinline__ void attn_block(const bf16x8 (&kf)[2][4], const bf16x
   // lane holds keys key0 + sb*16 + 4*lg + i of query ln
   float p[8];
   float mx = -INFINITY;
+  if (key0 + 32 <= n) {  // the whole block lies inside the sequence (wavefront-uniform)
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
+    for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int key = key0 + sb * 16 + 4 * lg + i;
-      const float v = key < n ? st[sb][i] * sl2e : -INFINITY;
-      p[sb * 4 + i] = v;
-      mx = fmaxf(mx, v);
-    }
+      for (int i = 0; i < 4; ++i) {
+        p[sb * 4 + i] = st[sb][i];
+        mx = fmaxf(mx, st[sb][i]);
+      }
+  } else {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = key0 + sb * 16 + 4 * lg + i;
+        const float v = key < n ? st[sb][i] : -INFINITY;
+        p[sb * 4 + i] = v;
+        mx = fmaxf(mx, v);
+      }
+  }
   mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(m_run, mx);
+  // running maximum of the scaled scores (the scale is positive, so it commutes with the max)
+  const float m_new = fmaxf(m_run, mx * sl2e);
   const float m_use = m_new == -INFINITY ? 0.f : m_new;
-  const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
+  // The accumulators are rescaled only in the blocks in which some query's maximum moved
+  // (wavefront-uniform test): with alpha == 1 for every lane the multiplications change nothing.
+  if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+    const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
+    l_run *= alpha;
+    m_run = m_new;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      o_acc[db][0] *= alpha;
+      o_acc[db][1] *= alpha;
+      o_acc[db][2] *= alpha;
+      o_acc[db][3] *= alpha;
+    }
+  }
   // probabilities as a bf16 pair (high part + remainder): the second product then carries
   // ~16 bits of each probability instead of 8
   float psum = 0.f;
   bf16x8 pf, pl;
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
-    const float e = exp2f(p[t] - m_use);
+    const float e = exp2f(fmaf(p[t], sl2e, -m_use));
     psum += e;
     const __bf16 hi = static_cast<__bf16>(e);
     pf[t] = hi;
     pl[t] = static_cast<__bf16>(e - static_cast<float>(hi));
   }
-  l_run = l_run * alpha + psum;
-  m_run = m_new;
-#pragma unroll
-  for (int db = 0; db < 8; ++db) {
-    o_acc[db][0] *= alpha;
-    o_acc[db][1] *= alpha;
-    o_acc[db][2] *= alpha;
-    o_acc[db][3] *= alpha;
-  }
+  l_run += psum;
   // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
 #pragma unroll
   for (int db = 0; db < 8; ++db) {
