@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2 (dual issue) x 2.4 GHz
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 FP32_VALU_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the streaming GEMM (reads + writes) from rocprofv3 --pmc FETCH_SIZE and
@@ -257,10 +258,13 @@ def main():
             t_fl = sum(g["flops"] for g in gemm) - ks["flops"]
             t_n = sum(g["launches"] for g in gemm) - ks["launches"]
             tf = t_fl / (t_ms * 1e-3) / 1e12 if t_ms > 0 else 0.0
+            f32 = cfg.dtype == "f32"   # float32 models run the plain vector-ALU GEMM
+            peak = FP32_VECTOR_PEAK_TFLOPS if f32 else MFMA_BF16_PEAK_TFLOPS
             result["roofline"] = {
-                "kernel": "k_gemm_fat / k_gemm_mid (every launch of the LDS-direct tile kernels)",
-                "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "launches": t_n,
+                "kernel": ("k_gemm_simple (float32, vector ALU)" if f32 else
+                           "k_gemm_fat / k_gemm_mid (every launch of the LDS-direct tile kernels)"),
+                "bound": "alu" if f32 else "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s",
+                "frac": tf / peak, "traffic": None, "launches": t_n,
                 "avg_launch_us": 1e3 * t_ms / max(t_n, 1), "event_overhead_us": 1e3 * ov_ms,
                 "flops_per_launch": t_fl / max(t_n, 1),
                 "share_of_kernel_time": t_ms / total_ms if total_ms > 0 else 0.0,
