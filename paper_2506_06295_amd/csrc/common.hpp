@@ -70,6 +70,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // of slices S it used (>= 1) so that consumers sum c_part[0..S) in order.  c_part holds
 // c_capacity floats; S is chosen so that S * M * N fits, and 0 is returned (nothing launched)
 // if not even M * N floats fit.
+// most float32 slices of the contraction index a GEMM launch may produce; the row kernels
+// dispatch their slice count to a compile-time constant in 1 .. kMaxSlices
+constexpr int kMaxSlices = 8;
 int gemm_max_slices();
 // slices launch_gemm would use for 16-byte aligned operands (0: capacity too small); host only
 int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity);

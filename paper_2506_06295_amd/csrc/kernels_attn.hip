@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
 // out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.
 // One wavefront per (query, head), two dims per lane.
 template <int SLOTS>
-__global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ part, int KS, int H_q,
+__global__ __launch_bounds__(64) void k_attn_merge(const float* __restrict__ part, int KS,
                                                    bf16_t* __restrict__ out) {
   const size_t qh = static_cast<size_t>(blockIdx.x);  // (b*Mq + iq)*H_q + a
   const float* w = part + qh * KS * (kDH + 2);
@@ -490,9 +490,9 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
                          H_kv, KS, oo, scratch);
     if (KS > 8)
       hipLaunchKernelGGL(k_attn_merge<kMaxKeySplit>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS,
-                         H_q, oo);
+                         oo);
     else if (KS > 1)
-      hipLaunchKernelGGL(k_attn_merge<8>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, H_q, oo);
+      hipLaunchKernelGGL(k_attn_merge<8>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, oo);
     return;
   }
   const size_t lds = static_cast<size_t>(d_h + n) * sizeof(float);

@@ -23,7 +23,6 @@ namespace dllmc {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-constexpr int kMaxSlices = 8;
 
 // Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest), and each XCD has
 // its own L2.  With several row tiles per column tile, remap (blockIdx.x, blockIdx.y) so that

@@ -63,7 +63,7 @@ template <> struct IO<bf16_t, 4> {
 // then spends its time in a chain of memory round trips.  So the count is dispatched to a
 // compile-time constant, every load of a row is issued unconditionally (columns past the end
 // are clamped to the last valid vector and their values ignored) and only then consumed.
-constexpr int kMaxSlicesRow = 8;
+static_assert(kMaxSlices == 8, "DLLMC_SWITCH_SLICES enumerates 1 .. 8 slices");
 
 #define DLLMC_SWITCH_SLICES(S, NS, ...)                   \
   switch (S) {                                            \
