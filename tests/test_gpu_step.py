@@ -369,3 +369,15 @@ def test_adaptive_step_replayed_from_a_captured_graph():
     assert all(torch.equal(a, b) for a, b in pairs)
     gpu.close()
     eager.close()
+
+
+def test_update_ratio_per_layer_combined_with_the_variants():
+    """Per-layer ratios together with K-verify, the L2 score and the selected-only update: every
+    layer sizes its staging and scatter by its own row count."""
+    cfg = MINI_LLADA.replace(T=4, K_p=3, K_r=4)
+    gpu, ora, st = run_schedule(cfg, stress=True, rho_layers=[0.6, 0.0, 0.25, 1.0], source="k", metric="l2",
+                                v_update="selected")
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= 2e-2
+    PU.compare_caches(cfg, gpu, ora, 2e-2)
+    gpu.close()
