@@ -6,16 +6,18 @@
 //
 //  * k_attn_simple -- any storage type / head width: one wavefront per (query, head), scores
 //                     kept in LDS, two passes.  Used for float32 models.
-//  * k_attn_mfma   -- bf16, head width 128.  Flash-style online softmax on
+//  * k_attn_mfma / k_attn_walk -- bf16, head width 128.  Flash-style online softmax on
 //                     v_mfma_f32_16x16x32_bf16.  The score tile is computed transposed
 //                     (S^T = K * Q^T) so that each lane ends up holding, for one query, eight
 //                     keys of a 32-key block: exactly the B-operand layout of the second
-//                     product O^T = V^T * P^T, so probabilities never leave registers.  K rows
-//                     are read straight from global memory (64 contiguous bytes per lane);
+//                     product O^T = V^T * P^T, so probabilities never leave registers.
 //                     V tiles are transposed once per workgroup through LDS and shared by
 //                     its four 16-query wavefronts.  With few queries (adaptive steps) the
 //                     key range is split over workgroups and k_attn_merge combines the
-//                     partial results in key-range order.
+//                     partial results in key-range order.  k_attn_mfma handles key ranges of
+//                     up to three blocks (all of it fetched into registers before the first
+//                     use), k_attn_walk longer ones (K and V tiles staged global -> LDS
+//                     several blocks ahead).
 #include "common.hpp"
 
 namespace dllmc {

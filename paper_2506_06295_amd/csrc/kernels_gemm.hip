@@ -5,12 +5,12 @@
 //                      float32 models and as the fallback for shapes the MFMA kernel
 //                      does not take).
 //  * k_gemm_stream  -- bf16 MFMA kernel built for the cached step's regime: few activation
-//                      rows (64 per workgroup tile) against a weight matrix that is read
+//                      rows (64 or 128 per workgroup tile) against a weight matrix that is read
 //                      exactly once from HBM.  The activation tile is staged in LDS, the
 //                      weight rows go straight from global memory into the MFMA B operand
 //                      (each lane reads 64 contiguous bytes of one weight row, so a
 //                      wavefront consumes whole 256-byte row segments), and the contraction
-//                      index is split over workgroups to put >= 2 workgroups on every CU.
+//                      index is split over workgroups so that every CU gets one.
 //                      Partial sums go to float32 slices that the row kernels add up in a
 //                      fixed order (no float atomics: results are bit-reproducible).
 //  * k_gemm_fat / k_gemm_mid -- bf16 MFMA kernels with 256 x 256 / 128 x 128 tiles whose
