@@ -664,9 +664,14 @@ GemmPlan plan_gemm(int dtype, bool operands_aligned, int lda, int M, int N, int 
     p.kind = 4;
     p.mt = (M + kMidM - 1) / kMidM;
     p.nt = N / kMidN;
-    // two workgroups per CU: aim at 512 tiles in flight, at least 8 steps of 64 per slice
-    int S = g_tune.force_s > 0 ? g_tune.force_s
-                               : (g_tune.target_wg + p.mt * p.nt - 1) / (p.mt * p.nt);
+    // Slices: as many as keep the launch within one workgroup per CU, rounded down (every
+    // slice costs its float32 partial sums twice, written here and read by the row kernel: a
+    // slightly underfilled chip is cheaper than a fifth slice), at least 8 steps of 64 each
+    // unless that leaves more than a fifth of the CUs without a workgroup
+    const int tiles = p.mt * p.nt;
+    int S = g_tune.target_wg / tiles;
+    if (5 * tiles * S <= 4 * g_tune.target_wg) ++S;
+    if (g_tune.force_s > 0) S = g_tune.force_s;
     S = S < 1 ? 1 : (S > s_cap ? s_cap : S);
     p.kps = ((K + S - 1) / S + kFatK - 1) / kFatK * kFatK;
     if (p.kps < 8 * kFatK) p.kps = 8 * kFatK;
