@@ -138,24 +138,26 @@ void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const
                        int d_kv, int d_h, const float2* rope_tab, void* k_cache, float* score,
                        int metric, void* k_stage, hipStream_t st);
 
-// Output-projection finalize over the carried rows: for i < Mc: row = carried[i]; ci = inv[row];
-// if ci >= 0: attn_cache[row] = T(sum_s c_part[s][ci][:]) (c_part slices hold M_R rows);
-// x[row] += attn_cache[row]; if ci >= 0: g_out[ci] = T(rmsnorm(x[row]) * gain).
-void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                       const int* carried, int Mc, const int* inv, void* attn_cache, float* x,
-                       const void* gain, void* g_out, hipStream_t st);
+// Output-projection finalize over the recomputed rows: for ci < M_R: row = rows_R[ci];
+// attn_cache[row] = T(sum_s c_part[s][ci][:]) (c_part slices hold M_R rows);
+// x[row] += attn_cache[row]; g_out[ci] = T(rmsnorm(x[row]) * gain).  The carried rows that are
+// not recomputed get their x[row] += attn_cache[row] in launch_down_finalize.
+void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows_R,
+                       int M_R, void* attn_cache, float* x, const void* gain, void* g_out,
+                       hipStream_t st);
 
 // SwiGLU: u[i][j] = T(silu(c[i][j]) * c[i][m + j]) with c = sum_s c_part[s] of width 2m.
 void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st);
 
-// Down-projection finalize over the carried rows: ffn_cache update like launch_o_finalize;
+// Down-projection finalize over the carried rows (row = carried[i], ci = inv[row]): if ci >= 0
+// the ffn_cache update as in launch_o_finalize, else first x[row] += attn_cache[row];
 // x[row] += ffn_cache[row]; then either h[row] = T(rmsnorm(x[row]) * next_gain) (next_gain
 // != nullptr) or, for the last layer, hidden_out[row] = T(x[row]) and, for prompt rows when
 // prompt_out != nullptr, prompt_out[seq][row % n] = T(x[row]).
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                          const int* carried, int Mc, const int* inv, void* ffn_cache, float* x,
-                          const void* next_gain, void* h, void* hidden_out, void* prompt_out,
-                          hipStream_t st);
+                          const int* carried, int Mc, const int* inv, const void* attn_cache,
+                          void* ffn_cache, float* x, const void* next_gain, void* h,
+                          void* hidden_out, void* prompt_out, hipStream_t st);
 
 // hidden_out[b][t] = prompt_out[b][t] for all prompt rows
 void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, void* hidden_out,

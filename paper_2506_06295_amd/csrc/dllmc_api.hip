@@ -409,8 +409,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       }
     }
     {
-      Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + esz) + M_R * d * (4.0 + 2.0 * esz), 0);
-      launch_o_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
+      Timed t(c, DLLMC_KC_ROW, M_R * d * (12.0 + 2.0 * esz), 0);
+      launch_o_finalize(ra, cws, S, rows_R, M_R, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
     }
     if (M_R > 0) {
       bool fused;
@@ -432,8 +432,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     }
     const bool last = (l == T - 1);
     {
-      Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + 2.0 * esz) + M_R * d * (4.0 + esz), 0);
-      launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(3, l), x,
+      Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + 2.0 * esz) + M_R * d * 4.0 + (Mc - M_R) * d * esz, 0);
+      launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), c->cache(3, l), x,
                            last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
                            (last && P) ? prompt_out : nullptr, st);
     }

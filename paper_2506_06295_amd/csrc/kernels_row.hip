@@ -342,40 +342,36 @@ __global__ __launch_bounds__(kThreads) void k_k_finalize(const float* __restrict
 }
 
 // ---- output projection epilogue + residual + FFN norm ------------------------------------
+// One workgroup per recomputed row.  Rows that are carried but not recomputed are left alone:
+// their residual add of the cached attention output happens in k_down_finalize, in the same
+// order of additions, so the stream x of such a row is read and written once per layer.
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict__ c_part, int S,
                                                          size_t slice_stride,
-                                                         const int* __restrict__ carried,
-                                                         const int* __restrict__ inv, int d,
+                                                         const int* __restrict__ rows_R, int d,
                                                          float eps, T* __restrict__ attn_cache,
                                                          float* __restrict__ x,
                                                          const T* __restrict__ gain,
                                                          T* __restrict__ g_out) {
   __shared__ float red[kNW];
-  const int row = carried[blockIdx.x];
-  const int ci = inv[row];
+  const int ci = blockIdx.x;
+  const int row = rows_R[ci];
   T* ac = attn_cache + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
   for (int c0 = 0; c0 < d; c0 += kChunk(V)) {
     Vec<V> a[kRegVecs], xv[kRegVecs];
-    if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, a);
+    sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, a);
 #pragma unroll
-    for (int it = 0; it < kRegVecs; ++it) {
-      const int c = chunk_col_clamped<V>(c0, it, d);
-      if (ci < 0) a[it] = IO<T, V>::ld(ac + c);
-      xv[it] = ld_f32<V>(xr + c);
-    }
+    for (int it = 0; it < kRegVecs; ++it) xv[it] = ld_f32<V>(xr + chunk_col_clamped<V>(c0, it, d));
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
       const int c = chunk_col<V>(c0, it);
       if (c < d) {
-        if (ci >= 0) {
 #pragma unroll
-          for (int e = 0; e < V; ++e) a[it].v[e] = roundf_to<T>(a[it].v[e]);
-          IO<T, V>::st(ac + c, a[it]);
-        }
+        for (int e = 0; e < V; ++e) a[it].v[e] = roundf_to<T>(a[it].v[e]);
+        IO<T, V>::st(ac + c, a[it]);
 #pragma unroll
         for (int e = 0; e < V; ++e) {
           xv[it].v[e] += a[it].v[e];
@@ -386,7 +382,6 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
       }
     }
   }
-  if (ci < 0) return;  // uniform over the workgroup
   // gain vectors of the first chunk: issued before the reduction so they arrive under it
   Vec<V> gk[kRegVecs];
 #pragma unroll
@@ -415,13 +410,14 @@ __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_down_finalize(
     const float* __restrict__ c_part, int S, size_t slice_stride, const int* __restrict__ carried,
-    const int* __restrict__ inv, int d, int n, int L_p, float eps, T* __restrict__ ffn_cache,
-    float* __restrict__ x, const T* __restrict__ next_gain, T* __restrict__ h,
+    const int* __restrict__ inv, int d, int n, int L_p, float eps,
+    const T* __restrict__ attn_cache, T* __restrict__ ffn_cache, float* __restrict__ x, const T* __restrict__ next_gain, T* __restrict__ h,
     T* __restrict__ hidden_out, T* __restrict__ prompt_out) {
   __shared__ float red[kNW];
   const int row = carried[blockIdx.x];
   const int ci = inv[row];
   T* fc = ffn_cache + static_cast<size_t>(row) * d;
+  const T* ac = attn_cache + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
@@ -431,8 +427,15 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
       const int c = chunk_col_clamped<V>(c0, it, d);
-      if (ci < 0) f[it] = IO<T, V>::ld(fc + c);
       xv[it] = ld_f32<V>(xr + c);
+      if (ci < 0) {
+        // a row that was not recomputed: the attention residual add that k_o_finalize left out
+        // comes first, then the FFN one below, as for a recomputed row
+        f[it] = IO<T, V>::ld(fc + c);
+        const Vec<V> a = IO<T, V>::ld(ac + c);
+#pragma unroll
+        for (int e = 0; e < V; ++e) xv[it].v[e] += a.v[e];
+      }
     }
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
@@ -608,17 +611,17 @@ void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const
                        P<float>(k_stage));
 }
 
-void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                       const int* carried, int Mc, const int* inv, void* attn_cache, float* x,
-                       const void* gain, void* g_out, hipStream_t st) {
-  if (Mc <= 0) return;
+void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows_R,
+                       int M_R, void* attn_cache, float* x, const void* gain, void* g_out,
+                       hipStream_t st) {
+  if (M_R <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
   const bool vec = vec_ok(a.d, {c_part, attn_cache, x, gain, g_out});
   if (a.dtype == 1) {
-    DLLMC_ROW_LAUNCH(k_o_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d, a.eps,
+    DLLMC_ROW_LAUNCH(k_o_finalize, bf16_t, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
                      P<bf16_t>(attn_cache), x, P<bf16_t>(gain), P<bf16_t>(g_out));
   } else {
-    DLLMC_ROW_LAUNCH(k_o_finalize, float, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d, a.eps,
+    DLLMC_ROW_LAUNCH(k_o_finalize, float, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
                      P<float>(attn_cache), x, P<float>(gain), P<float>(g_out));
   }
 }
@@ -636,19 +639,20 @@ void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u,
 }
 
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                          const int* carried, int Mc, const int* inv, void* ffn_cache, float* x,
-                          const void* next_gain, void* h, void* hidden_out, void* prompt_out,
-                          hipStream_t st) {
+                          const int* carried, int Mc, const int* inv, const void* attn_cache,
+                          void* ffn_cache, float* x, const void* next_gain, void* h,
+                          void* hidden_out, void* prompt_out, hipStream_t st) {
   if (Mc <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
-  const bool vec = vec_ok(a.d, {c_part, ffn_cache, x, next_gain, h, hidden_out, prompt_out});
+  const bool vec =
+      vec_ok(a.d, {c_part, attn_cache, ffn_cache, x, next_gain, h, hidden_out, prompt_out});
   if (a.dtype == 1) {
     DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
-                     a.n, a.L_p, a.eps, P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
+                     a.n, a.L_p, a.eps, P<bf16_t>(attn_cache), P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
                      P<bf16_t>(hidden_out), P<bf16_t>(prompt_out));
   } else {
     DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
-                     a.n, a.L_p, a.eps, P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
+                     a.n, a.L_p, a.eps, P<float>(attn_cache), P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
                      P<float>(hidden_out), P<float>(prompt_out));
   }
 }
