@@ -82,7 +82,7 @@ Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
   const size_t cws_floats = align_up(rows, 128) * n_max + static_cast<size_t>(640) * 128 * 128;
   L.cws_floats = cws_floats;
   L.off_cws = take(cws_floats * sizeof(float));
-  // split-key attention partials: only small query sets are split (at most 8 ways)
+  // split-key attention partials: only small query sets are split, the bound is the launcher's
   L.off_attn = take(attention_scratch_floats() * sizeof(float));
   L.off_scores = take(T * B * L_r * sizeof(float));
   L.off_carried = take(rows * sizeof(int));
