@@ -168,6 +168,15 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   const int klen = min(K, kbeg + k_per_slice) - kbeg;  // multiple of KH * KC
   const int hlen = klen / KH;                          // contraction range of one group
   const int nph = hlen / KC;
+  // DUAL: the walk starts at a phase that depends on the column tile and wraps around.  The
+  // workgroups of such a launch (one per CU, a single slice) run nearly in step, and rows of W
+  // are a multiple of 4 KB apart at these widths: unrotated, every load in flight on the chip
+  // has the same address bits below the row pitch and the memory channels are loaded unevenly
+  // (the launch took 48 to 61 us depending on where the two matrices happened to lie; rotated,
+  // 49 to 52 us everywhere).  The split launches already walk different ranges side by side
+  // and gain nothing; a single-slice launch with several workgroups per CU (the vocabulary
+  // projection) lost 10-35 %, so they keep the plain order.
+  const int rot = (DUAL && nph > 1) ? col_tile % nph : 0;
   // this wavefront's block of 16 columns; in a ragged last tile the blocks beyond N / 16 repeat
   // the last one (same loads, same barriers) and store nothing
   const int cb = col_tile * NWC + wcol;
@@ -211,7 +220,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j]);
+    if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j] + rot * KC);
     if (ain[j]) *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = v;
   }
   // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
@@ -223,17 +232,19 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     for (int t = 0; t < NS; ++t)
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + t * 128 + c * 32);
+        bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + rot * KC + t * 128 + c * 32);
   __syncthreads();
 
   for (int ph = 0; ph < nph; ++ph) {
     const bool more = ph + 1 < nph;
+    int pn = ph + 1 + rot;  // the phase fetched during this one
+    if (pn >= nph) pn -= nph;
     uint4 av[NCH];
     if (more) {
 #pragma unroll
       for (int j = 0; j < NCH; ++j) {
         av[j] = make_uint4(0u, 0u, 0u, 0u);
-        if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + (ph + 1) * KC);
+        if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + pn * KC);
       }
     }
     const bf16_t* ap = &As[ph & 1][kh][ln * LS];
@@ -245,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
         for (int c = 0; c < 4; ++c) bc[b][c] = bn[b][t][c];
       if (more) {
-        const int knext = (ph + 1) * KC + t * 128;
+        const int knext = pn * KC + t * 128;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
