@@ -542,6 +542,18 @@ __global__ __launch_bounds__(256) void k_gemm_mid_swiglu(const bf16_t* __restric
   gemm_lds_body<2, 2, 4, 4, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
 }
 
+// 256 rows x (48 gate + 48 up) columns, four wavefronts of 64 x 96 each: for up to 256 rows and
+// an FFN width that is a multiple of 48 the grid is one workgroup per 48 columns (12288 / 48 =
+// 256, one per CU), where the 128 x 128 tiles leave half of the CUs with twice the work (a
+// response refresh of 256 rows: 80 -> 69 us per layer; two workgroups of 128 x 96 per CU: 73).
+__global__ __launch_bounds__(256) void k_gemm_tall_swiglu(const bf16_t* __restrict__ A, int lda,
+                                                          const int* __restrict__ rows, int M,
+                                                          const bf16_t* __restrict__ Wg,
+                                                          const bf16_t* __restrict__ Wu, int N, int K,
+                                                          bf16_t* __restrict__ U) {
+  gemm_lds_body<4, 1, 4, 6, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
+}
+
 __global__ __launch_bounds__(256) void k_reduce_slices(const float* __restrict__ c_part, int S,
                                                        size_t MN, float* __restrict__ out) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -778,13 +790,17 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   if (M >= g_tune.tile_min_m && stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && K % kFatK == 0) {
     // many rows: the LDS-direct tile kernels with paired gate/up column blocks, one slice
     const bool fat = M >= g_tune.fat_min_m && m % (kFatN / 2) == 0;
-    if (fat || m % (kMidN / 2) == 0) {
+    const bool tall = !fat && M <= 256 && m % 48 == 0;
+    if (fat || tall || m % (kMidN / 2) == 0) {
       t_last_stream = false;
       const bf16_t* a = static_cast<const bf16_t*>(A);
       const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
       const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
       bf16_t* uo = static_cast<bf16_t*>(u);
-      if (fat)
+      if (tall)
+        hipLaunchKernelGGL(k_gemm_tall_swiglu, dim3(m / 48, 1, 1), dim3(256), 0, st, a, lda, rows, M,
+                           w0, w1, m, K, uo);
+      else if (fat)
         hipLaunchKernelGGL(k_gemm_fat_swiglu, dim3(m / (kFatN / 2), (M + kFatM - 1) / kFatM, 1),
                            dim3(512), 0, st, a, lda, rows, M, w0, w1, m, K, uo);
       else

@@ -132,6 +132,16 @@ def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
         binding.set_gemm_tuning(fat_min_m=1024)
 
 
+def test_fused_gate_up_in_the_tall_tile_kernel():
+    """224 rows per response refresh and an FFN width of 64 x 48: the 256 x 96 tile kernel."""
+    cfg = MINI_LLADA.replace(L_r=112, steps=4)
+    gpu, ora, st = run_schedule(cfg, stress=True, K_r=1)
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= 2e-2
+    PU.compare_caches(cfg, gpu, ora, 2e-2)
+    gpu.close()
+
+
 POLICIES = [dict(metric="l2"), dict(selection="random", seed=1234), dict(v_update="selected"),
             dict(metric="l2", v_update="selected"), dict(selection="random", seed=7, v_update="selected"),
             dict(source="k"), dict(source="k", metric="l2", v_update="selected")]
