@@ -146,7 +146,7 @@ template <int NW, int KC, int DUAL, int KH, int RB = 4>
 __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const bf16_t* __restrict__ A, int lda, const int* __restrict__ rows, int M,
     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1, int N0, int N, int K,
-    int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U) {
+    int k_per_slice, float* __restrict__ C, bf16_t* __restrict__ U, int n_full) {
   constexpr int LS = KC;                          // LDS row stride; chunk q of row r sits in slot
                                                   // q ^ (r % 16) of its group of 16 (no padding)
   constexpr int CPR = KC / 8;                     // 16-byte chunks per activation row and phase
@@ -177,11 +177,14 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   // and gain nothing; a single-slice launch with several workgroups per CU (the vocabulary
   // projection) lost 10-35 %, so they keep the plain order.
   const int rot = (DUAL && nph > 1) ? col_tile % nph : 0;
-  // this wavefront's block of 16 columns; in a ragged last tile the blocks beyond N / 16 repeat
-  // the last one (same loads, same barriers) and store nothing
-  const int cb = col_tile * NWC + wcol;
-  const bool active = cb * 16 < N;
-  const int ncol = (active ? cb : N / 16 - 1) * 16 + ln;
+  // This wavefront's block of 16 columns.  The first n_full column tiles own NWC blocks each, the
+  // others NWC - 1 (the host evens out the blocks per CU that way when a launch needs more than
+  // one round of workgroups); a wavefront without a block, also in a ragged last tile, only
+  // helps to stage the activations and keeps the barriers.
+  const int cb = col_tile < n_full ? col_tile * NWC + wcol
+                                   : n_full * NWC + (col_tile - n_full) * (NWC - 1) + wcol;
+  const bool active = (col_tile < n_full || wcol < NWC - 1) && cb * 16 < N;
+  const int ncol = (active ? cb : 0) * 16 + ln;
   const bf16_t* wp[NB];
   if (DUAL) {
     wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + kh * hlen + lg * 8;
@@ -226,13 +229,15 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
   constexpr int NS = KC / 128;
   uint4 bn[NB][NS][4];
+  if (active) {
 #pragma unroll
-  for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-    for (int t = 0; t < NS; ++t)
+      for (int t = 0; t < NS; ++t)
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + rot * KC + t * 128 + c * 32);
+        for (int c = 0; c < 4; ++c)
+          bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + rot * KC + t * 128 + c * 32);
+  }
   __syncthreads();
 
   for (int ph = 0; ph < nph; ++ph) {
@@ -248,6 +253,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
       }
     }
     const bf16_t* ap = &As[ph & 1][kh][ln * LS];
+    if (active) {
 #pragma unroll
     for (int t = 0; t < NS; ++t) {
       uint4 bc[NB][4];
@@ -274,6 +280,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
             acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                 af, __builtin_bit_cast(bf16x8, bc[b][c]), acc[b][mb], 0, 0, 0);
         }
+    }
     }
     if (more) {
 #pragma unroll
@@ -595,9 +602,9 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <int NW, int KC, int DUAL, int KH = 1, int RB = 4>
 void launch_stream(dim3 grid, hipStream_t st, const bf16_t* A, int lda, const int* rows, int M,
                    const bf16_t* W0, const bf16_t* W1, int N0, int N, int K, int kps, float* C,
-                   bf16_t* U) {
+                   bf16_t* U, int n_full = -1) {
   hipLaunchKernelGGL((k_gemm_stream<NW, KC, DUAL, KH, RB>), grid, dim3(NW * 64), 0, st, A, lda, rows, M, W0,
-                     W1, N0, N, K, kps, C, U);
+                     W1, N0, N, K, kps, C, U, n_full < 0 ? static_cast<int>(grid.x) : n_full);
 }
 
 bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const void* W1, int K) {
@@ -811,16 +818,39 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
   }
   if (!(stream_shape_ok(dtype, A, lda, w_gate, w_up, K) && m % 16 == 0) || M > 128) return false;
   const bool rows128 = g_tune.tall_max_m >= 128 && M > 64 && NW == 6 && KH == 2 && K % 256 == 0;
-  const dim3 grid((m + BN - 1) / BN, rows128 ? 1 : (M + 63) / 64, 1);
+  dim3 grid((m + BN - 1) / BN, rows128 ? 1 : (M + 63) / 64, 1);
+  // More workgroups than CUs (one runs per CU at a time): rather than rounds of full tiles with
+  // a last round that leaves CUs idle (FFN width 18944: 395 tiles of 48 columns, 2 x 48 columns
+  // on the busiest CU), whole rounds of workgroups of which the first n_full own NWC blocks of
+  // 16 columns and the others NWC - 1 (512 workgroups, 160 of them with 3 blocks: 48 + 32
+  // columns; 91 -> 86 us).  128-wide phases, which let two such workgroups share a CU, measured
+  // slower (90 us).
+  int n_full = -1;
+  {
+    static const int cus = [] {
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+        n = 256;
+      return n;
+    }();
+    const int NWC = NW / KH, nblk = m / 16;
+    const int G = (static_cast<int>(grid.x) + cus - 1) / cus * cus;
+    if (grid.y == 1 && NWC >= 2 && static_cast<int>(grid.x) > cus &&
+        static_cast<long long>(G) * (NWC - 1) <= nblk) {
+      n_full = nblk - G * (NWC - 1);
+      grid.x = G;
+    }
+  }
   t_last_stream = true;
   const bf16_t* a = static_cast<const bf16_t*>(A);
   const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
   const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
   bf16_t* uo = static_cast<bf16_t*>(u);
 #define DLLMC_GD(NWv, KCv, KHv) \
-  launch_stream<NWv, KCv, 1, KHv>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo)
+  launch_stream<NWv, KCv, 1, KHv>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo, n_full)
   if (rows128) {
-    launch_stream<6, 128, 1, 2, 8>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo);
+    launch_stream<6, 128, 1, 2, 8>(grid, st, a, lda, rows, M, w0, w1, m, m, K, K, nullptr, uo, n_full);
     return true;
   }
   switch (NW * 10 + KH) {

@@ -132,6 +132,17 @@ def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
         binding.set_gemm_tuning(fat_min_m=1024)
 
 
+def test_fused_gate_up_with_uneven_column_blocks():
+    """An FFN width of 18944 needs more 48-column workgroups (395) than the GPU has CUs, so the
+    launch hands out three or two blocks of 16 columns per workgroup (512 workgroups)."""
+    cfg = MINI_LONG.replace(m=18944, steps=4)
+    gpu, ora, st = run_schedule(cfg, stress=True)
+    assert st.failed == 0, st.failures
+    assert st.worst_rel <= 2e-2
+    PU.compare_caches(cfg, gpu, ora, 2e-2)
+    gpu.close()
+
+
 def test_fused_gate_up_in_the_tall_tile_kernel():
     """224 rows per response refresh and an FFN width of 64 x 48: the 256 x 96 tile kernel."""
     cfg = MINI_LLADA.replace(L_r=112, steps=4)
