@@ -108,12 +108,13 @@ struct RowKernelArgs {
 void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int* rows, int M,
                        const void* gain, float* x, void* h, hipStream_t st);
 
-// V finalize: for i < M: row = rows[i] (i if rows == nullptr); v = T(sum_s c_part[s][i][:]);
+// V finalize: for i < M: row = (i / per_seq) * n + first + i % per_seq, the carried rows of a
+// step (row = i when per_seq == 0); v = T(sum_s c_part[s][i][:]);
 // if score != nullptr and row is a response row: score[seq][j] = cos(v, v_cache[row]) (metric
 // 0) or -|v - v_cache[row]| (metric 1); then v_cache[row] = v, except that response rows go
 // to v_stage[i] instead when v_stage != nullptr (selected-only update, see launch_scatter_v).
-void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
-                       int d_kv, void* v_cache, float* score, int metric, void* v_stage,
+void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, int first, int per_seq,
+                       int M, int d_kv, void* v_cache, float* score, int metric, void* v_stage,
                        hipStream_t st);
 // v_cache[row] = v_stage[(row / n) * carried_per_seq + row % n - first] for the response rows
 // among rows_R[0..M_R)
@@ -149,13 +150,14 @@ void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const
 // SwiGLU: u[i][j] = T(silu(c[i][j]) * c[i][m + j]) with c = sum_s c_part[s] of width 2m.
 void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st);
 
-// Down-projection finalize over the carried rows (row = carried[i], ci = inv[row]): if ci >= 0
+// Down-projection finalize over the Mc carried rows (row = (i / per_seq) * n + first + i % per_seq,
+// ci = inv[row]): if ci >= 0
 // the ffn_cache update as in launch_o_finalize, else first x[row] += attn_cache[row];
 // x[row] += ffn_cache[row]; then either h[row] = T(rmsnorm(x[row]) * next_gain) (next_gain
 // != nullptr) or, for the last layer, hidden_out[row] = T(x[row]) and, for prompt rows when
 // prompt_out != nullptr, prompt_out[seq][row % n] = T(x[row]).
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                          const int* carried, int Mc, const int* inv, const void* attn_cache,
+                          int first, int per_seq, int Mc, const int* inv, const void* attn_cache,
                           void* ffn_cache, float* x, const void* next_gain, void* h,
                           void* hidden_out, void* prompt_out, hipStream_t st);
 

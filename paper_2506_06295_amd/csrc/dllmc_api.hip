@@ -369,7 +369,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
         launch_k_finalize(ra, cws, S, carried, Mc, d_kv, d_h, rope_tab, Tc, sc_out, c->metric,
                           defer_v ? abuf : nullptr, st);
       else
-        launch_v_finalize(ra, cws, S, carried, Mc, d_kv, Tc, sc_out, c->metric,
+        launch_v_finalize(ra, cws, S, P ? 0 : L_p, carried_per_seq, Mc, d_kv, Tc, sc_out, c->metric,
                           defer_v ? abuf : nullptr, st);
     }
     if (!Rf) {
@@ -433,7 +433,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     const bool last = (l == T - 1);
     {
       Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + 2.0 * esz) + M_R * d * 4.0 + (Mc - M_R) * d * esz, 0);
-      launch_down_finalize(ra, cws, S, M_R, carried, Mc, inv, c->cache(2, l), c->cache(3, l), x,
+      launch_down_finalize(ra, cws, S, M_R, P ? 0 : L_p, carried_per_seq, Mc, inv, c->cache(2, l), c->cache(3, l), x,
                            last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
                            (last && P) ? prompt_out : nullptr, st);
     }
@@ -573,7 +573,7 @@ int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache
                             static_cast<size_t>(rows) * d_kv * 8, st);
   if (S == 0) return DLLMC_ENOMEM;
   const RowKernelArgs ra{dtype, rows, 0, d, 0.f};
-  launch_v_finalize(ra, scratch, S, nullptr, rows, d_kv, v_cache, scores, 0, nullptr, st);
+  launch_v_finalize(ra, scratch, S, 0, 0, rows, d_kv, v_cache, scores, 0, nullptr, st);
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;
 }

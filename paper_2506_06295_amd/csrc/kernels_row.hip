@@ -198,14 +198,16 @@ __global__ __launch_bounds__(kThreads) void k_embed_norm(const T* __restrict__ h
 // Eq. (cos_sim); 1: minus the Euclidean distance, the paper's L2 variant), overwrite the cache --
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict__ c_part, int S,
-                                                         size_t slice_stride,
-                                                         const int* __restrict__ rows, int d_kv,
-                                                         int n, int L_p, T* __restrict__ v_cache,
+                                                         size_t slice_stride, int first,
+                                                         int per_seq, int d_kv, int n, int L_p,
+                                                         T* __restrict__ v_cache,
                                                          float* __restrict__ score, int metric,
                                                          T* __restrict__ v_stage) {
   __shared__ float red[kNW];
   const int i = blockIdx.x;
-  const int row = rows ? rows[i] : i;
+  // carried rows are positions first .. first + per_seq - 1 of every sequence (per_seq = 0: row i):
+  // computed, not looked up, so the cached row's loads go out together with the slices'
+  const int row = per_seq > 0 ? (i / per_seq) * n + first + i % per_seq : i;
   T* vc = v_cache + static_cast<size_t>(row) * d_kv;
   const int pos = row % n;
   const bool scored = (score != nullptr) && (pos >= L_p);
@@ -214,11 +216,11 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
   float dot = 0.f, nn = 0.f, no = 0.f;  // metric 1 (distance): dot holds sum (v - o)^2
   for (int c0 = 0; c0 < d_kv; c0 += kChunk(V)) {
     Vec<V> v[kRegVecs], o[kRegVecs];
-    sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv, c0, d_kv, v);
     if (scored) {
 #pragma unroll
       for (int it = 0; it < kRegVecs; ++it) o[it] = IO<T, V>::ld(vc + chunk_col_clamped<V>(c0, it, d_kv));
     }
+    sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(i) * d_kv, c0, d_kv, v);
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
       const int c = chunk_col<V>(c0, it);
@@ -409,33 +411,43 @@ __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c
 // ---- down projection epilogue + residual + next layer's attention norm / step output ------
 template <typename T, int V>
 __global__ __launch_bounds__(kThreads) void k_down_finalize(
-    const float* __restrict__ c_part, int S, size_t slice_stride, const int* __restrict__ carried,
+    const float* __restrict__ c_part, int S, size_t slice_stride, int first, int per_seq,
     const int* __restrict__ inv, int d, int n, int L_p, float eps,
-    const T* __restrict__ attn_cache, T* __restrict__ ffn_cache, float* __restrict__ x, const T* __restrict__ next_gain, T* __restrict__ h,
-    T* __restrict__ hidden_out, T* __restrict__ prompt_out) {
+    const T* __restrict__ attn_cache, T* __restrict__ ffn_cache, float* __restrict__ x,
+    const T* __restrict__ next_gain, T* __restrict__ h, T* __restrict__ hidden_out,
+    T* __restrict__ prompt_out) {
   __shared__ float red[kNW];
-  const int row = carried[blockIdx.x];
-  const int ci = inv[row];
+  // carried rows are positions first .. first + per_seq - 1 of every sequence: computed, so that
+  // the row's loads do not wait for a list entry
+  const int i = blockIdx.x;
+  const int row = (i / per_seq) * n + first + i % per_seq;
   T* fc = ffn_cache + static_cast<size_t>(row) * d;
   const T* ac = attn_cache + static_cast<size_t>(row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
   for (int c0 = 0; c0 < d; c0 += kChunk(V)) {
-    Vec<V> f[kRegVecs], xv[kRegVecs];
-    if (ci >= 0) sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, f);
+    // the stream and both cached rows are fetched before the row is known to be recomputed or
+    // not (one round trip for a row that is not; a recomputed one drops the cached values and
+    // fetches its slices in a second trip)
+    Vec<V> f[kRegVecs], a[kRegVecs], xv[kRegVecs];
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
       const int c = chunk_col_clamped<V>(c0, it, d);
       xv[it] = ld_f32<V>(xr + c);
-      if (ci < 0) {
-        // a row that was not recomputed: the attention residual add that k_o_finalize left out
-        // comes first, then the FFN one below, as for a recomputed row
-        f[it] = IO<T, V>::ld(fc + c);
-        const Vec<V> a = IO<T, V>::ld(ac + c);
+      f[it] = IO<T, V>::ld(fc + c);
+      a[it] = IO<T, V>::ld(ac + c);
+    }
+    const int ci = inv[row];
+    if (ci >= 0) {
+      sum_slices_chunk<V>(c_part, S, slice_stride, static_cast<size_t>(ci) * d, c0, d, f);
+    } else {
+      // a row that was not recomputed: the attention residual add that k_o_finalize left out
+      // comes first, then the FFN one below, as for a recomputed row
 #pragma unroll
-        for (int e = 0; e < V; ++e) xv[it].v[e] += a.v[e];
-      }
+      for (int it = 0; it < kRegVecs; ++it)
+#pragma unroll
+        for (int e = 0; e < V; ++e) xv[it].v[e] += a[it].v[e];
     }
 #pragma unroll
     for (int it = 0; it < kRegVecs; ++it) {
@@ -553,17 +565,17 @@ void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int*
   }
 }
 
-void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
-                       int d_kv, void* v_cache, float* score, int metric, void* v_stage,
+void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, int first, int per_seq,
+                       int M, int d_kv, void* v_cache, float* score, int metric, void* v_stage,
                        hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * d_kv;
   const bool vec = vec_ok(d_kv, {c_part, v_cache, v_stage});
   if (a.dtype == 1) {
-    DLLMC_ROW_LAUNCH(k_v_finalize, bf16_t, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
+    DLLMC_ROW_LAUNCH(k_v_finalize, bf16_t, vec, dim3(M), st, c_part, S, stride, first, per_seq, d_kv, a.n, a.L_p,
                      P<bf16_t>(v_cache), score, metric, P<bf16_t>(v_stage));
   } else {
-    DLLMC_ROW_LAUNCH(k_v_finalize, float, vec, dim3(M), st, c_part, S, stride, rows, d_kv, a.n, a.L_p,
+    DLLMC_ROW_LAUNCH(k_v_finalize, float, vec, dim3(M), st, c_part, S, stride, first, per_seq, d_kv, a.n, a.L_p,
                      P<float>(v_cache), score, metric, P<float>(v_stage));
   }
 }
@@ -639,7 +651,7 @@ void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u,
 }
 
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
-                          const int* carried, int Mc, const int* inv, const void* attn_cache,
+                          int first, int per_seq, int Mc, const int* inv, const void* attn_cache,
                           void* ffn_cache, float* x, const void* next_gain, void* h,
                           void* hidden_out, void* prompt_out, hipStream_t st) {
   if (Mc <= 0) return;
@@ -647,11 +659,11 @@ void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, in
   const bool vec =
       vec_ok(a.d, {c_part, attn_cache, ffn_cache, x, next_gain, h, hidden_out, prompt_out});
   if (a.dtype == 1) {
-    DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
+    DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<bf16_t>(attn_cache), P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
                      P<bf16_t>(hidden_out), P<bf16_t>(prompt_out));
   } else {
-    DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, carried, inv, a.d,
+    DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<float>(attn_cache), P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
                      P<float>(hidden_out), P<float>(prompt_out));
   }
