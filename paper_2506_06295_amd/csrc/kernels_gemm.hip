@@ -15,7 +15,9 @@
 //                      fixed order (no float atomics: results are bit-reproducible).
 //  * k_gemm_fat / k_gemm_mid -- bf16 MFMA kernels with 256 x 256 / 128 x 128 tiles whose
 //                      operands both go through LDS by direct global->LDS loads, for
-//                      launches with hundreds of activation rows.
+//                      launches with hundreds of activation rows; the same body with paired
+//                      gate/up column blocks and SwiGLU in the epilogue (k_gemm_*_swiglu,
+//                      k_gemm_tall_swiglu: 256 x 96 for up to 256 rows).
 #include "common.hpp"
 
 namespace dllmc {
