@@ -1,6 +1,6 @@
 """Parity at the headline workload's full size (LLaDA-8B shape: 32 layers, d 4096, L_p 512,
 L_r 256, bf16), in the launch configuration bench.py times: the first denoising steps of the
-schedule (a full refresh, then adaptive steps) on device-drawn random weights against the
+schedule (a full refresh, adaptive steps, a response refresh) on device-drawn random weights against the
 oracle, plus properties that hold at any size on the wider shapes (Dream-7B GQA widths, long
 prompt).  The oracle runs on the host cores; each test prints its progress.
 """
@@ -48,7 +48,7 @@ def test_llada8b_full_depth_first_steps_match_oracle():
                            cfg.K_r, storage="bf16")
     sched = I.TokenSchedule(cfg, stress=True)
     stats = PU.ParityStats()
-    for i in range(3):
+    for i in range(8):   # full refresh, six adaptive steps, the first response refresh (K_r = 7)
         PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, stats)
         print(f"[fullsize] step {i}: rel err {stats.rel_per_step[-1]:.3e}  t={time.time() - t0:.1f}s",
               flush=True)
