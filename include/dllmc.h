@@ -36,7 +36,8 @@ enum {
   DLLMC_EINVAL = -1, /* bad dimension, rho outside [0,1], K_p/K_r < 1, null or misaligned pointer */
   DLLMC_ESTATE = -2, /* first step is not step 0, or a non-zero step_idx that does not increase */
   DLLMC_EHIP = -3,   /* a HIP runtime call failed (see dllmc_last_hip_error) */
-  DLLMC_ENOMEM = -4  /* workspace smaller than dllmc_workspace_bytes() */
+  DLLMC_ENOMEM = -4, /* workspace smaller than dllmc_workspace_bytes() */
+  DLLMC_ETOOBIG = -5 /* dllmc_op_linear_static: M * N beyond the static scratch buffer */
 };
 
 /* Architecture of the bidirectional transformer (pre-RMSNorm, rotate-half RoPE with pairs
@@ -275,6 +276,20 @@ int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache
  * out: float32 [M, N]; scratch: device float32 [M * N * 8]. */
 int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_t M, const void* w,
                     int32_t N, int32_t K, float* out, float* scratch, void* hip_stream);
+
+/* dllmc_op_linear for callers that cannot allocate device memory or pass a scratch buffer
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * float32 slices of the split contraction go to a buffer that is part of the library's device
+ * image, 32 MiB on every GPU the library runs on, held until the process ends.  Same arguments
+ * and results as dllmc_op_linear without `scratch`; the call allocates nothing.
+ * M * N must not exceed dllmc_op_linear_static_max_elements() (8 Mi elements), else
+ * DLLMC_ETOOBIG and nothing is launched; up to 1 Mi elements the slices, and with them every
+ * bit of the result, are those of dllmc_op_linear.  All calls on one GPU share the one buffer:
+ * calls that may overlap on a GPU (different streams or host threads) race and must be
+ * serialised by the caller; calls on one stream are ordered. */
+size_t dllmc_op_linear_static_max_elements(void);
+int dllmc_op_linear_static(int32_t dtype, const void* a, const int32_t* row_idx, int32_t M,
+                           const void* w, int32_t N, int32_t K, float* out, void* hip_stream);
 
 /* Bidirectional attention of Mq query rows per sequence over all n cached keys of that
  * sequence, no mask (complexity appendix: the 4*r^*n*d term).  q, out: device [B, Mq, H_q*d_h];

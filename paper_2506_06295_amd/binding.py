@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdllmc.so")
 
 DLLMC_F32, DLLMC_BF16 = 0, 1
 _DTYPES = {"f32": (DLLMC_F32, torch.float32), "bf16": (DLLMC_BF16, torch.bfloat16)}
-_ERR = {-1: "EINVAL", -2: "ESTATE", -3: "EHIP", -4: "ENOMEM"}
+_ERR = {-1: "EINVAL", -2: "ESTATE", -3: "EHIP", -4: "ENOMEM", -5: "ETOOBIG"}
 
 EXPORTS = (
     "dllmc_workspace_bytes", "dllmc_create", "dllmc_num_selected", "dllmc_step",
@@ -29,6 +29,7 @@ EXPORTS = (
     "dllmc_gen_workspace_bytes", "dllmc_gen_create", "dllmc_gen_step", "dllmc_gen_read",
     "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head", "dllmc_set_policy",
     "dllmc_set_layer_rho", "dllmc_layer_num_selected", "dllmc_probe_copy", "dllmc_probe_read", "dllmc_probe_mfma",
+    "dllmc_op_linear_static", "dllmc_op_linear_static_max_elements",
 )
 NUM_KERNEL_CLASSES = 13
 
@@ -97,6 +98,11 @@ def lib() -> C.CDLL:
         L.dllmc_op_linear.restype = C.c_int
         L.dllmc_op_linear.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dllmc_op_linear_static.restype = C.c_int
+        L.dllmc_op_linear_static.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                             C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.dllmc_op_linear_static_max_elements.restype = C.c_size_t
+        L.dllmc_op_linear_static_max_elements.argtypes = []
         L.dllmc_op_attention.restype = C.c_int
         L.dllmc_op_attention.argtypes = [C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                          C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -383,6 +389,16 @@ def op_linear(dtype: str, a: torch.Tensor, w: torch.Tensor, row_idx: Optional[to
     _check(lib().dllmc_op_linear(_DTYPES[dtype][0], a.data_ptr(), _ptr(row_idx), M, w.data_ptr(), N, K,
                                  out.data_ptr(), scratch.data_ptr(), _stream_handle()),
            "dllmc_op_linear")
+    return out
+
+
+def op_linear_static(dtype: str, a: torch.Tensor, w: torch.Tensor, out: torch.Tensor,
+                     row_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dllmc_op_linear_static into the caller's `out` (float32 [M, N]); allocates nothing."""
+    M = a.shape[0] if row_idx is None else row_idx.numel()
+    _check(lib().dllmc_op_linear_static(_DTYPES[dtype][0], a.data_ptr(), _ptr(row_idx), M, w.data_ptr(),
+                                        w.shape[0], a.shape[1], out.data_ptr(), _stream_handle()),
+           "dllmc_op_linear_static")
     return out
 
 

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -530,6 +531,7 @@ const char* dllmc_strerror(int code) {
     case DLLMC_ESTATE: return "call out of order (step 0 first, then increasing step_idx)";
     case DLLMC_EHIP: return "HIP runtime error";
     case DLLMC_ENOMEM: return "workspace too small";
+    case DLLMC_ETOOBIG: return "problem larger than the library's static scratch buffer";
     default: return "unknown error";
   }
 }
@@ -589,6 +591,62 @@ int dllmc_op_linear(int32_t dtype, const void* a, const int32_t* row_idx, int32_
                             static_cast<size_t>(M) * N * 8, st);
   if (S == 0) return DLLMC_ENOMEM;
   launch_reduce_slices(scratch, S, M, N, out, st);
+  HIP_TRY(hipGetLastError());
+  return DLLMC_OK;
+}
+
+// ---- gathered linear map for callers that cannot allocate ---------------------------------
+// The float32 slices of the split contraction live in a file-scope device array instead of a
+// caller-provided buffer.  In host code the array's name is only a stand-in: its device address
+// is looked up once per device (with that device current) and kept.
+}  // extern "C"
+
+constexpr size_t kStaticScratchFloats = static_cast<size_t>(8) << 20;  // 32 MiB per GPU
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_static_scratch_ptr[kMaxDevices] = {};
+std::mutex g_static_scratch_mu;
+
+// device address of `scratch` on the current device (nullptr + HIP error on failure)
+hipError_t static_scratch_on_current_device(float** out) {
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+  if (!g_static_scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_scratch_ptr[dev] = p;
+  }
+  *out = g_static_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" {
+
+size_t dllmc_op_linear_static_max_elements(void) { return kStaticScratchFloats; }
+
+int dllmc_op_linear_static(int32_t dtype, const void* a, const int32_t* row_idx, int32_t M,
+                           const void* w, int32_t N, int32_t K, float* out, void* hip_stream) {
+  if ((dtype != DLLMC_F32 && dtype != DLLMC_BF16) || !a || !w || !out || M < 1 || N < 1 || K < 1)
+    return DLLMC_EINVAL;
+  if (static_cast<size_t>(M) * N > kStaticScratchFloats) return DLLMC_ETOOBIG;
+  (void)hipGetLastError();
+  float* ptr = nullptr;
+  HIP_TRY(static_scratch_on_current_device(&ptr));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // every slice the launch produces is written whole before it is read: nothing to clear
+  const int S = launch_gemm(dtype, a, K, row_idx, M, w, nullptr, N, N, K, ptr,
+                            kStaticScratchFloats, st);
+  if (S == 0) return DLLMC_ETOOBIG;
+  launch_reduce_slices(ptr, S, M, N, out, st);
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;
 }
