@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdllmc.so")
-SOURCES = ("kernels_gemm.hip", "kernels_row.hip", "kernels_select.hip", "kernels_attn.hip", "kernels_gen.hip", "kernels_probe.hip",
+SOURCES = ("kernels_gemm.hip", "kernels_row.hip", "kernels_select.hip", "kernels_attn.hip", "kernels_gen.hip", "kernels_probe.hip", "kernels_fused.hip",
            "dllmc_api.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -61,6 +61,38 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// ---- MFMA operand types, tile-to-XCD mapping, explicit waits ----------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest), and each XCD has
+// its own L2.  With several row tiles per column tile, remap (blockIdx.x, blockIdx.y) so that
+// all row tiles of one column tile run back to back on the same XCD: the weight tile is then
+// fetched from HBM once and the other row tiles hit in that XCD's L2.  The column tiles beyond
+// the last multiple of 8 are walked column by column after the remapped part.
+__device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
+  const int nt = gridDim.x, mt = gridDim.y;
+  col_tile = blockIdx.x;
+  row_tile = blockIdx.y;
+  if (mt > 1 && nt >= 8) {
+    const int nt8 = nt & ~7;
+    const int lin = blockIdx.x + nt * blockIdx.y;
+    if (lin < nt8 * mt) {
+      const int xcd = lin & 7, slot = lin >> 3;
+      row_tile = slot % mt;
+      col_tile = (slot / mt) * 8 + xcd;
+    } else {
+      const int rest = lin - nt8 * mt;
+      row_tile = rest % mt;
+      col_tile = nt8 + rest / mt;
+    }
+  }
+}
+// s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // ---- host-side launchers (defined in the kernels_*.hip files) --------------------------
 // dtype: 0 = float32 storage, 1 = bf16 storage.  All pointers are device pointers.
 
@@ -82,6 +114,7 @@ void gemm_set_fat_min_m(int m);
 void gemm_set_tall_max_m(int m);
 // True when the most recent launch_gemm / launch_gemm_swiglu of this thread ran k_gemm_stream.
 bool gemm_last_was_stream();
+void gemm_clear_last_stream();  // a matrix product launched by another launcher follows
 int launch_gemm(int dtype, const void* A, int lda, const int* rows, int M, const void* W0,
                 const void* W1, int N0, int N, int K, float* c_part, size_t c_capacity,
                 hipStream_t st);
@@ -170,9 +203,28 @@ void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, v
 //   sel_out[b*sel_stride + pos] = j                          (if sel_out != nullptr)
 //   rows_out[b*per_seq + off + pos] = b*n + L_p + j          (if rows_out != nullptr)
 //   inv_out[b*n + L_p + j] = b*per_seq + off + pos, and -1 for rows not selected
-void launch_select(const float* scores, int B, int L, int k, int* sel_out, int sel_stride,
+// part != nullptr: the scores are formed first (and written to `scores`) from the sums the
+// fused V-verify launch left per row and column tile (n_ct tiles, see launch_vverify_fused).
+void launch_select(float* scores, int B, int L, int k, int* sel_out, int sel_stride,
                    int* rows_out, int per_seq, int off, int* inv_out, int n, int L_p,
-                   hipStream_t st);
+                   hipStream_t st, const float* part = nullptr, int n_ct = 0, int part_stride = 0,
+                   int metric = 0);
+
+// Fused V-verify (bf16): v = bf16(A[row(i)] W^T) for the M carried rows (row(i) = (i / per_seq) * n
+// + first + i % per_seq, or i when per_seq == 0); when part != nullptr, for every response row
+// (position >= L_p) and 64-column tile t the sums (v . old, |v|^2, |old|^2) (metric 1: (|v -
+// old|^2, 0, 0)) over the tile's columns go to part[(c * n_ct + t) * part_stride + seq * (n -
+// L_p) + pos - L_p]; then v_cache[row] = v.  vverify_fused_ok says whether the shape is handled.
+bool vverify_fused_ok(int dtype, const void* A, int lda, int M, const void* W, int N, int K,
+                      const void* v_cache);
+size_t vverify_part_floats(int N, size_t scored_rows);
+int vverify_col_tiles(int N);
+void launch_vverify_fused(const void* A, int lda, int M, int first, int per_seq, int n, int L_p,
+                          const void* W, int N, int K, void* v_cache, float* part, int part_stride,
+                          int metric, hipStream_t st);
+// score[i] = cosine (metric 0) or minus distance (metric 1) from the tile sums, i < count
+void launch_scores_from_part(const float* part, int n_ct, int count, int metric, float* score,
+                             hipStream_t st);
 
 // Attention of Mq compact queries per sequence over all n keys of that sequence.
 // q, out: [B, Mq, H_q*d_h]; k_cache, v_cache: [B, n, H_kv*d_h].

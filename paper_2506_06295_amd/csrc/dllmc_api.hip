@@ -49,7 +49,7 @@ struct Layout {
   size_t cws_floats;  // capacity of the GEMM slice buffer
   size_t cache_k, cache_v, cache_ao, cache_fo;  // per-layer strides inside their regions
   size_t off_k, off_v, off_ao, off_fo, off_prompt_out, off_x, off_h, off_q, off_a, off_g, off_u,
-      off_cws, off_attn, off_scores, off_carried, off_rows, off_inv, off_rope, total;
+      off_cws, off_attn, off_scores, off_part, off_carried, off_rows, off_inv, off_rope, total;
 };
 
 Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
@@ -86,6 +86,8 @@ Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
   // split-key attention partials: only small query sets are split, the bound is the launcher's
   L.off_attn = take(attention_scratch_floats() * sizeof(float));
   L.off_scores = take(T * B * L_r * sizeof(float));
+  // per (response row, column tile) sums of the fused V-verify launch
+  L.off_part = take(vverify_part_floats(static_cast<int>(d_kv), B * L_r) * sizeof(float));
   L.off_carried = take(rows * sizeof(int));
   L.off_rows = take(rows * sizeof(int));
   L.off_inv = take(rows * sizeof(int));
@@ -305,6 +307,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   float* cws = c->at<float>(c->lay.off_cws);
   const size_t cws_cap = c->lay.cws_floats;
   float* scores = c->at<float>(c->lay.off_scores);
+  float* part = c->at<float>(c->lay.off_part);
   void* prompt_out = c->ws + c->lay.off_prompt_out;
   const float2* rope_tab = c->at<float2>(c->lay.off_rope);
 
@@ -352,18 +355,29 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     // scored against the cache, cache overwritten.  Refresh steps always go V first.
     const bool ksrc = c->source_k && !Rf;
     void* Tc = ksrc ? Kc : Vc;   // cache of the verified tensor
-    int S;
-    {
+    int S = 1;
+    float* sc = scores + static_cast<size_t>(l) * B * L_r;
+    // selected-only update: the response rows' new rows wait in the attention output buffer
+    // (free until this layer's attention) for the selection
+    const bool defer_v = c->v_selected_only && !Rf;
+    // The default method in one launch: projection, rounding, the sums of Eq. (cos_sim) per row
+    // and column tile, cache overwrite; the selection kernel forms the scores.
+    const bool fused_v = !ksrc && !defer_v && vverify_fused_ok(dt, h, d, Mc, w.wv, d_kv, d, Vc);
+    const bool part_scores = fused_v && !Rf && !c->random_sel;
+    if (fused_v) {
+      Timed t(c, DLLMC_KC_GEMM_V, (static_cast<double>(d_kv) * d + static_cast<double>(Mc) * d) * esz +
+                                      (Rf ? 1.0 : 2.0) * Mc * d_kv * esz,
+              gemm_flops(Mc, d_kv, d));
+      gemm_clear_last_stream();
+      launch_vverify_fused(h, d, Mc, P ? 0 : L_p, carried_per_seq, n, L_p, w.wv, d_kv, d, Vc,
+                           part_scores ? part : nullptr, B * L_r, c->metric, st);
+    } else {
       Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
       S = launch_gemm(dt, h, d, carried, Mc, ksrc ? w.wk : w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap,
                       st);
       if (S == 0) return DLLMC_ENOMEM;
     }
-    float* sc = scores + static_cast<size_t>(l) * B * L_r;
-    // selected-only update: the response rows' new rows wait in the attention output buffer
-    // (free until this layer's attention) for the selection
-    const bool defer_v = c->v_selected_only && !Rf;
-    {
+    if (!fused_v) {
       Timed t(c, DLLMC_KC_ROW, Mc * d_kv * (4.0 + 2.0 * esz), 0);
       float* sc_out = (Rf || c->random_sel) ? nullptr : sc;
       if (ksrc)
@@ -378,7 +392,8 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       if (c->random_sel) launch_random_scores(c->seed, step_idx, l, B, L_r, sc, st);
       launch_select(sc, B, L_r, k_l,
                     sel_idx ? sel_idx + static_cast<size_t>(l) * B * L_r : nullptr, L_r, rows_R,
-                    per_seq, sel_off, inv, n, L_p, st);
+                    per_seq, sel_off, inv, n, L_p, st, part_scores ? part : nullptr,
+                    vverify_col_tiles(d_kv), B * L_r, c->metric);
       if (defer_v)
         launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Tc, st);
     }
@@ -558,7 +573,8 @@ int dllmc_op_select(const float* scores, int32_t B, int32_t L, int32_t k, int32_
                     void* hip_stream) {
   if (!scores || B < 1 || L < 1 || k < 0 || k > L || (k > 0 && !idx_out)) return DLLMC_EINVAL;
   (void)hipGetLastError();
-  launch_select(scores, B, L, k, idx_out, k, nullptr, 0, 0, nullptr, L, 0,
+  // without tile sums the scores are only read
+  launch_select(const_cast<float*>(scores), B, L, k, idx_out, k, nullptr, 0, 0, nullptr, L, 0,
                 static_cast<hipStream_t>(hip_stream));
   HIP_TRY(hipGetLastError());
   return DLLMC_OK;
@@ -571,6 +587,13 @@ int dllmc_op_vverify(int32_t dtype, const void* h, const void* wv, void* v_cache
     return DLLMC_EINVAL;
   (void)hipGetLastError();
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (vverify_fused_ok(dtype, h, d, rows, wv, d_kv, d, v_cache) &&
+      vverify_part_floats(d_kv, rows) <= static_cast<size_t>(rows) * d_kv * 8) {
+    launch_vverify_fused(h, d, rows, 0, 0, rows, 0, wv, d_kv, d, v_cache, scratch, rows, 0, st);
+    launch_scores_from_part(scratch, vverify_col_tiles(d_kv), rows, 0, scores, st);
+    HIP_TRY(hipGetLastError());
+    return DLLMC_OK;
+  }
   const int S = launch_gemm(dtype, h, d, nullptr, rows, wv, nullptr, d_kv, d_kv, d, scratch,
                             static_cast<size_t>(rows) * d_kv * 8, st);
   if (S == 0) return DLLMC_ENOMEM;

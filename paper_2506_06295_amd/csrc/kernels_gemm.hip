@@ -22,33 +22,7 @@
 
 namespace dllmc {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-
-// Workgroups are handed to the 8 XCDs round-robin in launch order (x fastest), and each XCD has
-// its own L2.  With several row tiles per column tile, remap (blockIdx.x, blockIdx.y) so that
-// all row tiles of one column tile run back to back on the same XCD: the weight tile is then
-// fetched from HBM once and the other row tiles hit in that XCD's L2.  The column tiles beyond
-// the last multiple of 8 are walked column by column after the remapped part.
-__device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
-  const int nt = gridDim.x, mt = gridDim.y;
-  col_tile = blockIdx.x;
-  row_tile = blockIdx.y;
-  if (mt > 1 && nt >= 8) {
-    const int nt8 = nt & ~7;
-    const int lin = blockIdx.x + nt * blockIdx.y;
-    if (lin < nt8 * mt) {
-      const int xcd = lin & 7, slot = lin >> 3;
-      row_tile = slot % mt;
-      col_tile = (slot / mt) * 8 + xcd;
-    } else {
-      const int rest = lin - nt8 * mt;
-      row_tile = rest % mt;
-      col_tile = nt8 + rest / mt;
-    }
-  }
-}
 int gemm_max_slices() { return kMaxSlices; }
 
 // ------------------------------------------------------------------------------------
@@ -293,9 +267,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   }
 
   if (KH > 1) {
-    // hand-over of the second group's sums: [column wavefront][matrix][accumulator element][lane]
-    // (every LDS read of the activation tiles is behind the barrier that ended the last phase)
+    // hand-over of the other groups' sums: [group - 1][column wavefront][matrix][accumulator
+    // element][lane] (every LDS read of the activation tiles is behind the barrier that ended the
+    // last phase); the first group adds them to its own in group order
     float* red = reinterpret_cast<float*>(&As[0][0][0]);
+    static_assert((KH - 1) * NWC * NB * 4 * RB * 64 * sizeof(float) <= sizeof(As), "hand-over fits the tiles");
     if (kh > 0) {
 #pragma unroll
       for (int b = 0; b < NB; ++b)
@@ -303,17 +279,19 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
         for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            red[((wcol * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
+            red[((((kh - 1) * NWC + wcol) * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane] = acc[b][mb][i];
     }
     __syncthreads();
     if (kh > 0 || !active) return;
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int g = 1; g < KH; ++g)
 #pragma unroll
-      for (int mb = 0; mb < RB; ++mb)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          acc[b][mb][i] += red[((wcol * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane];
+        for (int mb = 0; mb < RB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            acc[b][mb][i] += red[((((g - 1) * NWC + wcol) * NB + b) * (4 * RB) + mb * 4 + i) * 64 + lane];
   }
 
   if (!active) return;
@@ -357,11 +335,6 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 //        enough tiles to fill the chip when M is a few hundred rows.
 constexpr int kFatM = 256, kFatN = 256, kFatK = 64;
 constexpr int kMidM = 128, kMidN = 128;
-
-// s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-}
 
 //   PAIR = 1 (fused gate/up + SwiGLU, single slice): the tile's weight rows are BN/2 rows of W0
 //        (gate) followed by the same BN/2 rows of W1 (up), so every lane ends up with the gate
@@ -617,6 +590,7 @@ bool stream_shape_ok(int dtype, const void* A, int lda, const void* W0, const vo
 
 static thread_local bool t_last_stream = false;
 bool gemm_last_was_stream() { return t_last_stream; }
+void gemm_clear_last_stream() { t_last_stream = false; }
 
 void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
 void gemm_set_tall_max_m(int m) { if (m >= 0) g_tune.tall_max_m = m; }

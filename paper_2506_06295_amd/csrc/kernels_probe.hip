@@ -9,8 +9,6 @@ namespace dllmc {
 namespace {
 
 constexpr int kThreads = 256;
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 // dst[i] = src[i], 16 bytes per lane per trip, four independent trips in flight per lane
 __global__ __launch_bounds__(kThreads) void k_probe_copy(const uint4* __restrict__ src,

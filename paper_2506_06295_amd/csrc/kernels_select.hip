@@ -47,22 +47,104 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratc
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kThreads) void k_select(const float* __restrict__ scores, int L, int k,
+// part != nullptr: the scores are formed here first, from the sums the fused V-verify kernel left
+// per (row, column tile): part[(c * n_ct + tile) * part_stride + b * L + j], c = 0 dot product (or
+// squared distance), 1 |new|^2, 2 |old|^2, added in tile order; Eq. (cos_sim) with the
+// denominator clamped at 1e-8, or minus the distance (metric 1).  They are written to `scores`.
+__global__ __launch_bounds__(kThreads) void k_select(float* scores, int L, int k,
                                                      int* __restrict__ sel_out, int sel_stride,
                                                      int* __restrict__ rows_out, int per_seq,
                                                      int off, int* __restrict__ inv_out, int n,
-                                                     int L_p) {
+                                                     int L_p, const float* __restrict__ part,
+                                                     int n_ct, int part_stride, int metric) {
   __shared__ uint32_t hist[256];
   __shared__ uint32_t scan_scratch[kNW + 1];
   __shared__ uint32_t sh_prefix, sh_need;
-  __shared__ uint32_t keys[kKeysInLds];
+  __shared__ __attribute__((aligned(16))) uint32_t keys[kKeysInLds];
+  __shared__ __attribute__((aligned(16))) float psum[kNW][3][kThreads];
   const int b = blockIdx.x;
-  const float* s = scores + static_cast<size_t>(b) * L;
+  float* s = scores + static_cast<size_t>(b) * L;
   // The five passes below read every key; one trip to global memory instead of five when the
   // sequence fits the LDS buffer (the visibility of `keys` rides on the first barrier below).
   const bool in_lds = L <= kKeysInLds;
-  if (in_lds)
+  if (part != nullptr) {
+    const size_t comp = static_cast<size_t>(n_ct) * part_stride;
+    const bool vec = (L % 4 == 0) && (part_stride % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(part) & 15u) == 0;
+    if (vec) {
+      // A lane takes four neighbouring rows (16-byte loads) and a wavefront a quarter of the
+      // column tiles, up to 16 tiles x 3 sums requested before the first is added, so that the
+      // whole table is in flight at once; the wavefronts' sums meet in LDS and are added in
+      // wavefront order (= tile order).
+      const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+      const int per = (n_ct + kNW - 1) / kNW;
+      const int t0 = w * per, t1 = min(n_ct, t0 + per);
+      for (int j0 = 0; j0 < L; j0 += 4 * kWave) {
+        const int jl = j0 + 4 * lane;
+        const bool rv = jl < L;
+        const float* p0 = part + static_cast<size_t>(b) * L + (rv ? jl : 0);
+        float4 acc[3];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c0 = t0; c0 < t1; c0 += 16) {
+          float4 v[3][16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) {
+            const size_t ct = static_cast<size_t>(min(c0 + u, t1 - 1)) * part_stride;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) v[c][u] = *reinterpret_cast<const float4*>(p0 + c * comp + ct);
+          }
+#pragma unroll
+          for (int u = 0; u < 16; ++u)
+            if (c0 + u < t1) {
+#pragma unroll
+              for (int c = 0; c < 3; ++c) {
+                acc[c].x += v[c][u].x;
+                acc[c].y += v[c][u].y;
+                acc[c].z += v[c][u].z;
+                acc[c].w += v[c][u].w;
+              }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 3; ++c) *reinterpret_cast<float4*>(&psum[w][c][4 * lane]) = acc[c];
+        __syncthreads();
+        const int j = j0 + static_cast<int>(threadIdx.x);
+        if (j < L) {
+          float dot = psum[0][0][threadIdx.x], nn = psum[0][1][threadIdx.x], no = psum[0][2][threadIdx.x];
+#pragma unroll
+          for (int ww = 1; ww < kNW; ++ww) {
+            dot += psum[ww][0][threadIdx.x];
+            nn += psum[ww][1][threadIdx.x];
+            no += psum[ww][2][threadIdx.x];
+          }
+          const float sc = metric == 0 ? dot / fmaxf(sqrtf(nn) * sqrtf(no), 1e-8f) : -sqrtf(dot);
+          s[j] = sc;
+          if (in_lds) keys[j] = order_key(sc);
+        }
+        __syncthreads();
+      }
+    } else {
+      for (int j = threadIdx.x; j < L; j += kThreads) {
+        const float* p0 = part + static_cast<size_t>(b) * L + j;
+        float dot = 0.f, nn = 0.f, no = 0.f;
+        for (int ct = 0; ct < n_ct; ++ct) {
+          dot += p0[static_cast<size_t>(ct) * part_stride];
+          nn += p0[comp + static_cast<size_t>(ct) * part_stride];
+          no += p0[2 * comp + static_cast<size_t>(ct) * part_stride];
+        }
+        const float sc = metric == 0 ? dot / fmaxf(sqrtf(nn) * sqrtf(no), 1e-8f) : -sqrtf(dot);
+        s[j] = sc;
+        if (in_lds) keys[j] = order_key(sc);
+      }
+    }
+    if (!in_lds) {  // the passes below re-read the scores this workgroup has just written
+      __threadfence_block();
+      __syncthreads();
+    }
+  } else if (in_lds) {
     for (int j = threadIdx.x; j < L; j += kThreads) keys[j] = order_key(s[j]);
+  }
   if (k <= 0) __syncthreads();
 
   uint32_t kth = 0, need = 0;
@@ -148,12 +230,12 @@ void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, floa
                      seed, static_cast<uint32_t>(step), static_cast<uint32_t>(layer), B, L, out);
 }
 
-void launch_select(const float* scores, int B, int L, int k, int* sel_out, int sel_stride,
+void launch_select(float* scores, int B, int L, int k, int* sel_out, int sel_stride,
                    int* rows_out, int per_seq, int off, int* inv_out, int n, int L_p,
-                   hipStream_t st) {
+                   hipStream_t st, const float* part, int n_ct, int part_stride, int metric) {
   if (B <= 0 || L <= 0) return;
   hipLaunchKernelGGL(k_select, dim3(B), dim3(kThreads), 0, st, scores, L, k, sel_out, sel_stride,
-                     rows_out, per_seq, off, inv_out, n, L_p);
+                     rows_out, per_seq, off, inv_out, n, L_p, part, n_ct, part_stride, metric);
 }
 
 }  // namespace dllmc

@@ -63,15 +63,20 @@ class Shadow:
 
 # ---- tolerances derived from a floor -----------------------------------------------------
 FROB_FACTOR, ROW_FACTOR, MAXABS_FACTOR = 1.5, 2.0, 2.0
-FROB_EPS = 2e-5      # added to a bar so that floors of a few 1e-5 (rare last-bit flips) stay usable
+# Added to a bar so that floors made of a handful of last-bit differences stay usable.  bf16: a
+# float32 sum taken in another order (matrix-core tiles, split contraction) than the shadow's
+# moves up to ~1e-3 of the elements of a tensor across a bf16 rounding boundary, each by one ulp
+# (2^-8 relative): a Frobenius ratio of 2^-8 sqrt(1e-3).  float32: summation-order noise itself.
+EPS = {"bf16": 2.0 ** -8 * 1e-3 ** 0.5, "f32": 2e-6}
 
 
-def bars(entry: Dict[str, float]) -> Dict[str, float]:
+def bars(entry: Dict[str, float], dtype: str = "bf16") -> Dict[str, float]:
     """Largest admissible distances of an implementation from the float64 oracle for a tensor
     whose oracle-only floor is `entry`."""
-    return {"frob": FROB_FACTOR * entry["frob"] + FROB_EPS,
-            "row": ROW_FACTOR * entry["row"] + 2 * FROB_EPS,
-            "maxabs": MAXABS_FACTOR * entry["maxabs"] + 8 * FROB_EPS}
+    eps = EPS[dtype]
+    return {"frob": FROB_FACTOR * entry["frob"] + eps,
+            "row": ROW_FACTOR * entry["row"] + 2 * eps,
+            "maxabs": MAXABS_FACTOR * entry["maxabs"] + 8 * eps}
 
 
 def band(score_dev: float, base: float = 1e-4) -> float:

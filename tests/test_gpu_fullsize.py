@@ -4,8 +4,6 @@ schedule (a full refresh, adaptive steps, a response refresh) on device-drawn ra
 oracle, plus properties that hold at any size on the wider shapes (Dream-7B GQA widths, long
 prompt).  The oracle runs on the host cores; each test prints its progress.
 """
-import json
-import os
 import time
 
 import numpy as np
@@ -27,45 +25,76 @@ def make_gpu(cfg, weights, **over):
         rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
 
 
-def noise_floor():
-    """How far two valid bf16 evaluations of this model are apart (oracle with float32 vs float64
-    accumulation; tests/golden/make_bf16_noise_floor.py): no implementation can be closer to the
-    oracle than that, so the bar at depth is max(2e-2, 1.25 x floor)."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "bf16_noise_floor_llada8b.json")
-    return json.load(open(path))
-
-
 def test_llada8b_full_depth_first_steps_match_oracle():
+    """All four step kinds at the headline size: a full refresh, six adaptive steps, the first
+    response refresh (K_r = 7) and, with K_p lowered to 8, a step that refreshes the prompt while
+    the response is updated adaptively.  Every layer's four cache tensors and the step output are
+    held to bars derived from the oracle-only noise floor of that very tensor."""
     cfg = I.CONFIGS["llada8b"]
-    floor = noise_floor()
-    bar = lambda f: max(2e-2, 1.25 * f)
+    floor = PU.load_floor("llada8b")
+    K_p = 8
     t0 = time.time()
     dev_w = I.device_weights(cfg)
     host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]   # float32, 28 GB
     print(f"\n[fullsize] weights ready {time.time() - t0:.1f}s", flush=True)
-    gpu = make_gpu(cfg, dev_w)
-    ora = O.CachedDenoiser(PU.oracle_model(cfg), host_w, cfg.B, cfg.L_p, cfg.L_r, cfg.rho, cfg.K_p,
+    gpu = make_gpu(cfg, dev_w, K_p=K_p)
+    ora = O.CachedDenoiser(PU.oracle_model(cfg), host_w, cfg.B, cfg.L_p, cfg.L_r, cfg.rho, K_p,
                            cfg.K_r, storage="bf16")
     sched = I.TokenSchedule(cfg, stress=True)
-    stats = PU.ParityStats()
-    for i in range(8):   # full refresh, six adaptive steps, the first response refresh (K_r = 7)
+    stats = PU.ParityStats(floor=floor)
+    kinds = []
+    for i in range(9):
         PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, stats)
-        print(f"[fullsize] step {i}: rel err {stats.rel_per_step[-1]:.3e}  t={time.time() - t0:.1f}s",
+        kinds.append(("P" if i % K_p == 0 else "-") + ("R" if i % cfg.K_r == 0 else "a"))
+        print(f"[fullsize] step {i} [{kinds[-1]}]: rel err {stats.rel_per_step[-1]:.3e}  t={time.time() - t0:.1f}s",
               flush=True)
+    assert kinds == ["PR"] + ["-a"] * 6 + ["-R", "Pa"]
     print(f"[fullsize] selection exact={stats.exact} tied_same={stats.tied_same} "
-          f"followed={stats.followed} failed={stats.failed}; worst |ds| {stats.worst_score_dev:.2e}",
-          flush=True)
+          f"followed={stats.followed} failed={stats.failed}; worst |ds| {stats.worst_score_dev:.2e} "
+          f"({stats.worst_score_dev_over_tol:.2f} of its tolerance)", flush=True)
+    assert stats.failed == 0, stats.failures
+    # 7 adaptive steps x 32 layers: nearly every margin is decisive under the stressed schedule
+    assert stats.exact >= 188 and stats.followed <= 4
+    assert stats.worst_rel <= PU.stated_tol(cfg)
+    PU.compare_caches(cfg, gpu, ora, stats, verbose=True)
+    print(f"[fullsize] worst distance / bar over all tensors: {stats.worst_over_bar:.2f}", flush=True)
+    last = floor["layers"][cfg.T - 1]["FFNOut"]["frob"]
+    print(f"[fullsize] note: the last layers' FFNOut floors exceed the stated 2e-2 (layer {cfg.T - 1}: "
+          f"{last:.3e} between two oracle evaluations); those tensors are held to 1.5 x floor", flush=True)
+    gpu.close()
+
+
+WIDE = [("dream7b", None), ("llada8b_long", None), ("llada8b_b16", [3, 12])]
+
+
+@pytest.mark.parametrize("name,seqs", WIDE, ids=[w[0] for w in WIDE])
+def test_wide_shapes_match_oracle_at_full_width(name, seqs):
+    """Full width and length, two layers, against the oracle: a full refresh, two adaptive steps,
+    a response refresh and a prompt refresh with adaptive response (K_p = 4, K_r = 3), i.e. the
+    grouped-KV Dream widths (d 3584, FFN 18944), the 4608-row long prompt, and two of the sixteen
+    batched sequences.  Bars from tests/golden/noise_floor_<name>_T2.json (oracle only)."""
+    cfg = I.CONFIGS[name].replace(T=2)
+    floor = PU.load_floor(f"{name}_T2")
+    K_p, K_r = floor["K_p"], floor["K_r"]
+    t0 = time.time()
+    dev_w = I.device_weights(cfg)
+    host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]
+    gpu = make_gpu(cfg, dev_w, K_p=K_p, K_r=K_r)
+    nb = cfg.B if seqs is None else len(seqs)
+    ora = O.CachedDenoiser(PU.oracle_model(cfg), host_w, nb, cfg.L_p, cfg.L_r, cfg.rho, K_p, K_r,
+                           storage="bf16")
+    sched = I.TokenSchedule(cfg, stress=True)
+    stats = PU.ParityStats(floor=floor)
+    for i in range(len(floor["step_kinds"])):
+        PU.run_step_pair(cfg, gpu, ora, sched.hidden_in(i), i, stats, seqs=seqs)
+        print(f"\n[{name}] step {i} [{floor['step_kinds'][i]}]: rel err {stats.rel_per_step[-1]:.3e}  "
+              f"t={time.time() - t0:.1f}s", flush=True)
+    PU.compare_caches(cfg, gpu, ora, stats, seqs=seqs, verbose=True)
+    print(f"[{name}] selection exact={stats.exact} tied_same={stats.tied_same} followed={stats.followed}; "
+          f"worst |ds| {stats.worst_score_dev:.2e}; worst distance / bar {stats.worst_over_bar:.2f}", flush=True)
     assert stats.failed == 0, stats.failures
     assert stats.exact > 0
-    assert stats.worst_rel <= bar(floor["hidden_out"])
-    assert stats.worst_score_dev <= PU.score_tol(cfg)
-    # cache tensors of the first, a middle and the last layer
-    for l in (0, cfg.T // 2, cfg.T - 1):
-        for which, name in ((0, "K"), (1, "V"), (2, "AttnOut"), (3, "FFNOut")):
-            got = gpu.read_cache(l, which).float().cpu().numpy()
-            e = PU.rel_err(got, getattr(ora, name)[l])
-            print(f"[fullsize] layer {l} {name}: rel err {e:.3e} (floor {floor[f'layer{l}'][name]:.3e})", flush=True)
-            assert e <= bar(floor[f"layer{l}"][name]), (l, name, e)
+    assert stats.worst_rel <= PU.stated_tol(cfg)
     gpu.close()
 
 
@@ -165,7 +194,7 @@ def test_llada8b_closed_loop_first_steps_match_oracle():
     from oracle import dllm_generate_oracle as G
     from tests.test_gpu_generate import run_loop
     cfg = I.CONFIGS["llada8b"]
-    floor = noise_floor()
+    floor = PU.load_floor("llada8b")
     t0 = time.time()
     dev_w = I.device_weights(cfg)
     host_w = [{k: v.float().cpu().numpy() for k, v in w.items()} for w in dev_w]
@@ -178,8 +207,7 @@ def test_llada8b_closed_loop_first_steps_match_oracle():
     ggen = binding.Generator(gpu, hw["embed"], hw["final_norm_g"], hw["lm_head"], cfg.steps)
     ogen = G.Generator(ora, host_hw["embed"], host_hw["final_norm_g"], host_hw["lm_head"], cfg.vocab,
                        cfg.steps)
-    st, tally, tokens = run_loop(cfg, steps=2, loop=(gpu, ora, ggen, ogen),
-                                 act_tol=max(2e-2, 1.25 * floor["hidden_out"]))
+    st, tally, tokens = run_loop(cfg, steps=2, loop=(gpu, ora, ggen, ogen), floor=floor)
     print(f"[fullsize loop] rel {st.worst_rel:.3e} {tally} selection exact/tied/followed/failed "
           f"{st.exact}/{st.tied_same}/{st.followed}/{st.failed}  t={time.time() - t0:.1f}s", flush=True)
     assert st.failed == 0, st.failures
