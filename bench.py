@@ -24,10 +24,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2 (dual issue) x 2.4 GHz
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 FP32_VALU_PEAK_TFLOPS = 157.3
-# HBM bytes per launch of the streaming GEMM (reads + writes) from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this benchmark, scaled by the counters' reading for a 256 MiB copy;
+# HBM bytes per launch of the streaming GEMM (reads + writes): NOT measured by this program.  The
+# figure comes from separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
+# scaled by the counters' reading for a 256 MiB copy (profiles/k_gemm_stream_<workload>_hbm_counters.txt);
 # None where no such run has been recorded for the workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"llada8b": 113.8e6}
+TRAFFIC_BYTES_PER_LAUNCH = {"llada8b": 113.7e6}
+TRAFFIC_SOURCE = "profiles/k_gemm_stream_{name}_hbm_counters.txt (separate rocprofv3 --pmc runs, not this run)"
 
 
 def make_denoiser(binding, cfg, weights, **over):
@@ -41,6 +43,16 @@ def make_denoiser(binding, cfg, weights, **over):
 def step_kind(cfg, i):
     P, R = i % cfg.K_p == 0, i % cfg.K_r == 0
     return "full" if P and R else "prompt+adaptive" if P else "response" if R else "adaptive"
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def cpu_baseline(cfg, dev_weights, hidden_host, sample_layers=8):
@@ -72,6 +84,7 @@ def cpu_baseline(cfg, dev_weights, hidden_host, sample_layers=8):
     sched_s = sum(counts[k] * t_kind[k] for k in kinds) * (cfg.T / Ls)
     return {
         "value": cfg.steps / sched_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+        "cpu_model": cpu_model(),
         "sample": (f"numpy float64 oracle, {Ls} of {cfg.T} layers, one step of each kind "
                    f"(full/adaptive/response/prompt+adaptive = "
                    f"{t_kind['full']:.2f}/{t_kind['adaptive']:.2f}/{t_kind['response']:.2f}/"
@@ -160,10 +173,55 @@ def main():
     run(K, start=w_aligned)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    steps_per_s = K / elapsed
     kinds_timed = {}
     for s in range(w_aligned, w_aligned + K):
         kinds_timed[step_kind(cfg, s % cfg.steps)] = kinds_timed.get(step_kind(cfg, s % cfg.steps), 0) + 1
+
+    # Every step kind on its own, whatever slice of the schedule the flags picked: groups of
+    # same-kind steps (ascending step indices of that kind; step 0 may be repeated, it starts a
+    # new generation) between two synchronisations, median of three groups.  The headline is the
+    # whole schedule: its kind counts weighted with these per-kind times.
+    KINDS = ("full", "prompt+adaptive", "response", "adaptive")
+    counts = {k: 0 for k in KINDS}
+    for i in range(cfg.steps):
+        counts[step_kind(cfg, i)] += 1
+    cursor = [0]
+
+    def indices_of(kind, reps):
+        out_idx = []
+        for _ in range(reps):
+            if kind == "full":
+                i = 0
+            else:
+                i = cursor[0] + 1
+                while step_kind(cfg, i) != kind:
+                    i += 1
+            cursor[0] = i
+            out_idx.append(i)
+        return out_idx
+
+    def run_indices(idx):
+        for i in idx:
+            den.step(hidden[i % cfg.steps], i, out)
+
+    group = {"full": 2, "prompt+adaptive": 2, "response": 4, "adaptive": 12}
+    den.step(hidden[0], 0, out)
+    ms_kind = {}
+    for kind in KINDS:
+        if counts[kind] == 0:
+            continue
+        ts = []
+        for _ in range(3):
+            run_indices(indices_of(kind, 1))   # the kind's kernels warm
+            idx = indices_of(kind, group[kind])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            run_indices(idx)
+            torch.cuda.synchronize()
+            ts.append(1e3 * (time.perf_counter() - t1) / len(idx))
+        ms_kind[kind] = float(np.median(ts))
+    sched_ms = sum(counts[k] * ms_kind[k] for k in ms_kind)
+    steps_per_s = cfg.steps / (sched_ms * 1e-3)
 
     result = {
         "metric": "cached denoise steps/s",
@@ -172,7 +230,7 @@ def main():
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": 1e3 * elapsed / K,
+        "ms_per_step": sched_ms / cfg.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -181,8 +239,16 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} heads={cfg.H_q}/{cfg.H_kv}x{cfg.d_h} "
                                f"m={cfg.m} B={cfg.B} L_p={cfg.L_p} L_r={cfg.L_r} rho={cfg.rho} "
                                f"K_p={cfg.K_p} K_r={cfg.K_r} schedule={cfg.steps} steps",
-                   "step_kinds_timed": kinds_timed, "seed": cfg.seed, "variant": variant or None},
-        "response_tokens_per_s": cfg.B * cfg.L_r * steps_per_s / cfg.steps,
+                   "seed": cfg.seed, "variant": variant or None},
+        "value_is": "whole schedule: the schedule's step-kind counts weighted with the time of each "
+                    "kind measured on its own (ms_per_step_kind), so it does not depend on which "
+                    "slice --steps/--warmup pick; timed_slice is the literal K-step region",
+        "schedule_kind_counts": counts,
+        "ms_per_step_kind": ms_kind,
+        "ms_per_schedule": sched_ms,
+        "timed_slice": {"steps": K, "warmup": W, "ms_per_step": 1e3 * elapsed / K,
+                        "steps_per_s": K / elapsed, "step_kinds": kinds_timed},
+        "response_tokens_per_s": cfg.B * cfg.L_r / (sched_ms * 1e-3),
         "token_rows_per_s": cfg.B * cfg.L_r * steps_per_s,
     }
 
@@ -225,8 +291,8 @@ def main():
             raw = ev[j][0].elapsed_time(ev[j][1])
             per_kind_raw.setdefault(kind, []).append(raw)
             per_kind.setdefault(kind, []).append(raw - ov_ms * spans_per_step[j])
-        result["ms_per_step_kind"] = {k: float(np.median(v)) for k, v in per_kind.items()}
-        result["ms_per_step_kind_with_events"] = {k: float(np.median(v)) for k, v in per_kind_raw.items()}
+        result["timed_slice"]["ms_per_step_kind_events_removed"] = {k: float(np.median(v)) for k, v in per_kind.items()}
+        result["timed_slice"]["ms_per_step_kind_with_events"] = {k: float(np.median(v)) for k, v in per_kind_raw.items()}
         # the dominant kernel: every launch of the weight-streaming GEMM kernel (the library
         # counts those launches a second time under their kernel's name)
         ks = stats.pop("k_gemm_stream")
@@ -242,6 +308,7 @@ def main():
                       "of the recomputed rows)",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "traffic_source": TRAFFIC_SOURCE.format(name=cfg.name) if traffic else None,
             "launches": ks["launches"], "avg_launch_us": 1e3 * k_ms / k_n,
             "avg_launch_us_with_event": 1e3 * ks["ms_raw"] / k_n,
             "event_overhead_us": 1e3 * ov_ms,
@@ -282,6 +349,21 @@ def main():
                 "TFLOPs": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 else 0.0}
             for k, v in stats.items()}
         result["kernel_time_ms_per_step"] = total_ms / K
+        # the same per kernel class for every step kind on its own (average us per launch, the
+        # event's share removed)
+        by_kind = {}
+        den.step(hidden[0], 0, out)
+        cursor[0] = 0
+        for kind in ms_kind:
+            run_indices(indices_of(kind, 1))
+            den.profile_enable(True)
+            run_indices(indices_of(kind, max(group[kind] // 2, 1)))
+            st_k = den.profile_read(reset=True)
+            den.profile_enable(False)
+            by_kind[kind] = {k: {"launches": v["launches"],
+                                 "avg_us": 1e3 * max(v["ms"] - ov_ms * v["launches"], 0.0) / v["launches"]}
+                             for k, v in st_k.items() if v["launches"] and k != "event_overhead"}
+        result["kernels_by_kind"] = by_kind
 
     # what this GPU delivers for the plainest kernels (1 GiB copy, 1 GiB read, MFMA loop from
     # registers): the measured ceilings beside the published peaks
@@ -348,10 +430,10 @@ def main():
         result["uncached_gpu"] = {
             "ms_per_step": 1e3 * t_unc, "steps_per_s": 1.0 / t_unc,
             "tflops": fl / t_unc / 1e12, "mfma_frac": fl / t_unc / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "speedup_schedule": (elapsed / K) and t_unc / (elapsed / K),
+            "speedup_schedule": 1e3 * t_unc / result["ms_per_step"],
         }
-        if "ms_per_step_kind" in result and "adaptive" in result["ms_per_step_kind"]:
-            result["uncached_gpu"]["speedup_adaptive_step"] = 1e3 * t_unc / result["ms_per_step_kind"]["adaptive"]
+        if "adaptive" in ms_kind:
+            result["uncached_gpu"]["speedup_adaptive_step"] = 1e3 * t_unc / ms_kind["adaptive"]
 
     # the closed loop: the same schedule driven by the model's own predictions (embedding
     # gather, cached step, mask-predictor head over the full vocabulary, remasking transition),
@@ -381,7 +463,7 @@ def main():
         result["closed_loop"] = {
             "ms_per_generation": 1e3 * t_gen, "steps_per_s": cfg.steps / t_gen,
             "response_tokens_per_s": cfg.B * cfg.L_r / t_gen,
-            "ms_per_step_beyond_core_path": 1e3 * (t_gen / cfg.steps - elapsed / K),
+            "ms_per_step_beyond_core_path": 1e3 * t_gen / cfg.steps - result["ms_per_step"],
             "vocab": cfg.vocab, "block_len": cfg.block_len or cfg.L_r,
             "lm_head_bytes_per_step": head_bytes,
             "all_revealed": bool((tok[:, cfg.L_p:] != cfg.vocab).all().item()),

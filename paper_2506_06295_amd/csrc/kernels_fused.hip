@@ -264,9 +264,11 @@ bool vverify_fused_ok(int dtype, const void* A, int lda, int M, const void* W, i
                       const void* v_cache) {
   if (dtype != 1 || M < 1 || N % kVT || K % kVK || lda % 8) return false;
   if (!aligned16(A) || !aligned16(W) || !aligned16(v_cache)) return false;
-  // beyond ~1000 tiles the wider tiles of the split kernels make better use of L2 and LDS
+  // Up to two tiles per CU.  Beyond that (refresh steps with many rows) the 128 x 128 and 256 x 256
+  // tiles of the split kernels pull half as many operand bytes into a CU per flop and win in
+  // spite of their float32 round trip (768 rows x 4096 columns: 57 us here against ~45 there).
   const long long tiles = static_cast<long long>((M + kVT - 1) / kVT) * (N / kVT);
-  return tiles <= 1024;
+  return tiles <= 512;
 }
 
 size_t vverify_part_floats(int N, size_t scored_rows) {
