@@ -85,6 +85,58 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
                  int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- paged cache layout ------------------------------------------------------------------
+ * The paper's Limitations paragraph names the growth of the feature caches with the sequence
+ * length as its open problem and points at memory management as the remedy.  Here the four
+ * per-layer cache tensors of Sec. 3.2 may live in a POOL of equally sized pages instead of one
+ * flat [B, n, width] block per layer: a page holds page_rows consecutive token positions of one
+ * sequence, in every layer and in all four tensors (one page id addresses the same slot
+ * everywhere), and a page table maps (sequence b, logical page p) to a pool page:
+ *     row (b, pos) of a layer's cache tensor  ->  row page_table[b][pos / page_rows] * page_rows
+ *                                                     + pos % page_rows of that tensor's pool block.
+ * Results are bit-identical to the flat layout.  The pool may be carved from the context's own
+ * workspace (pool == NULL) or be caller-owned device memory of dllmc_pool_bytes() bytes shared
+ * by several contexts of the same model, page_rows and pool_pages, each using its own, disjoint
+ * pages: when a generation is over its pages can serve another context (eviction is the
+ * caller's policy; dllmc_pool_* below is a host-side allocator for the ids).
+ * Pool block layout: regions K, V, AttnOut, FFNOut in this order; a region holds n_layers
+ * blocks of pool_pages * page_rows rows of the tensor's width, each block 256-byte aligned. */
+typedef struct {
+  int32_t page_rows;          /* token positions per page, >= 1 */
+  int32_t pool_pages;         /* pages in the pool */
+  const int32_t* page_table;  /* HOST [B][ceil((L_p + L_r) / page_rows)], copied; entries in
+                                 [0, pool_pages), no page listed twice */
+  void* pool;                 /* device, 256-byte aligned, or NULL: inside the workspace */
+  size_t pool_bytes;          /* size of `pool` (ignored when pool == NULL) */
+} dllmc_paging;
+
+/* Bytes of a pool block for this model (0: invalid arguments). */
+size_t dllmc_pool_bytes(const dllmc_model* model, int32_t page_rows, int32_t pool_pages);
+/* dllmc_workspace_bytes / dllmc_create for the paged layout.  With paging->pool == NULL the
+ * workspace also holds the pool.  DLLMC_EINVAL on a malformed page table. */
+size_t dllmc_workspace_bytes_paged(const dllmc_model* model, int32_t L_p, int32_t L_r,
+                                   const dllmc_paging* paging);
+int dllmc_create_paged(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                       int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r,
+                       const dllmc_paging* paging, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+/* Replace the page table of a paged context (HOST array as above, copied; waits for the
+ * context's stream).  Page contents are not moved: the caches are void afterwards and the next
+ * dllmc_step must be step 0 (DLLMC_ESTATE otherwise).  DLLMC_EINVAL for a flat context or a
+ * malformed table (nothing changes then). */
+int dllmc_set_page_table(dllmc_ctx* ctx, const int32_t* page_table);
+
+/* Host-side allocator of page ids (no device memory involved; thread-safe).  alloc hands out
+ * `count` ids, lowest free ids first, all or nothing (DLLMC_ENOMEM); free takes ids back and
+ * rejects, without freeing anything, a list with an id that is out of range, not allocated or
+ * listed twice (DLLMC_EINVAL). */
+typedef struct dllmc_page_pool dllmc_page_pool;
+int dllmc_pool_create(dllmc_page_pool** out, int32_t pool_pages);
+int32_t dllmc_pool_available(dllmc_page_pool* pool);
+int dllmc_pool_alloc(dllmc_page_pool* pool, int32_t count, int32_t* ids_out);
+int dllmc_pool_free(dllmc_page_pool* pool, const int32_t* ids, int32_t count);
+int dllmc_pool_destroy(dllmc_page_pool* pool);
+
 /* floor(rho * L_r): rows recomputed per sequence and layer on an adaptive step (Sec. 3.2.2). */
 int32_t dllmc_num_selected(const dllmc_ctx* ctx);
 
@@ -172,7 +224,8 @@ const char* dllmc_kernel_class_name(int32_t cls);
 int dllmc_destroy(dllmc_ctx* ctx);
 
 const char* dllmc_strerror(int code);
-/* hipError_t value of the most recent failed HIP call in this process, 0 if none. */
+/* hipError_t value of the most recent failed HIP call made by the library on the calling thread,
+ * 0 if none. */
 int dllmc_last_hip_error(void);
 
 /* ---- closed denoising loop around the cached step -------------------------------------
@@ -231,8 +284,11 @@ int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_
                   const void* final_norm_g, float eps, const void* lm_head, int32_t vocab, int32_t d,
                   void* scratch, int32_t* x0, float* conf, void* hip_stream);
 
-/* Tuning knobs of the bf16 streaming GEMM (process-wide; an argument outside its range leaves
- * that knob unchanged): nw wavefronts per workgroup (4|8) of the single-matrix kernel; nw_dual
+/* Tuning knobs of the bf16 matrix products, for tests and measurements.  The call changes the
+ * process default (thread-safe); a context copies the default when it is created and keeps its
+ * copy for life, so live contexts are not affected; the single operations (dllmc_op_*) and the
+ * closed loop's head use the default in force when they are called.  An argument outside its
+ * range leaves that knob unchanged: nw wavefronts per workgroup (4|8) of the single-matrix kernel; nw_dual
  * shape of the fused gate/up kernel: 4|8 wavefronts in one group, or 100 + (4|6|8): the
  * wavefronts form two groups that each walk one half of the contraction range (default 106:
  * 48 columns of each matrix per workgroup); force_s number of contraction slices

@@ -30,6 +30,8 @@ EXPORTS = (
     "dllmc_gen_destroy", "dllmc_op_head_scratch_bytes", "dllmc_op_head", "dllmc_set_policy",
     "dllmc_set_layer_rho", "dllmc_layer_num_selected", "dllmc_probe_copy", "dllmc_probe_read", "dllmc_probe_mfma",
     "dllmc_op_linear_static", "dllmc_op_linear_static_max_elements",
+    "dllmc_pool_bytes", "dllmc_workspace_bytes_paged", "dllmc_create_paged", "dllmc_set_page_table",
+    "dllmc_pool_create", "dllmc_pool_available", "dllmc_pool_alloc", "dllmc_pool_free", "dllmc_pool_destroy",
 )
 NUM_KERNEL_CLASSES = 13
 
@@ -44,6 +46,11 @@ class dllmc_model(C.Structure):
 class dllmc_layer_weights(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in ("attn_norm_g", "wq", "wk", "wv", "wo", "ffn_norm_g",
                                           "w_gate", "w_up", "w_down")]
+
+
+class dllmc_paging(C.Structure):
+    _fields_ = [("page_rows", C.c_int32), ("pool_pages", C.c_int32), ("page_table", C.POINTER(C.c_int32)),
+                ("pool", C.c_void_p), ("pool_bytes", C.c_size_t)]
 
 
 class dllmc_gen_config(C.Structure):
@@ -75,6 +82,28 @@ def lib() -> C.CDLL:
         L.dllmc_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(dllmc_model),
                                    C.POINTER(dllmc_layer_weights), C.c_int32, C.c_int32, C.c_float,
                                    C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.dllmc_pool_bytes.restype = C.c_size_t
+        L.dllmc_pool_bytes.argtypes = [C.POINTER(dllmc_model), C.c_int32, C.c_int32]
+        L.dllmc_workspace_bytes_paged.restype = C.c_size_t
+        L.dllmc_workspace_bytes_paged.argtypes = [C.POINTER(dllmc_model), C.c_int32, C.c_int32,
+                                                  C.POINTER(dllmc_paging)]
+        L.dllmc_create_paged.restype = C.c_int
+        L.dllmc_create_paged.argtypes = [C.POINTER(C.c_void_p), C.POINTER(dllmc_model),
+                                         C.POINTER(dllmc_layer_weights), C.c_int32, C.c_int32, C.c_float,
+                                         C.c_int32, C.c_int32, C.POINTER(dllmc_paging), C.c_void_p,
+                                         C.c_size_t, C.c_void_p]
+        L.dllmc_set_page_table.restype = C.c_int
+        L.dllmc_set_page_table.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+        L.dllmc_pool_create.restype = C.c_int
+        L.dllmc_pool_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
+        L.dllmc_pool_available.restype = C.c_int32
+        L.dllmc_pool_available.argtypes = [C.c_void_p]
+        L.dllmc_pool_alloc.restype = C.c_int
+        L.dllmc_pool_alloc.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+        L.dllmc_pool_free.restype = C.c_int
+        L.dllmc_pool_free.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
+        L.dllmc_pool_destroy.restype = C.c_int
+        L.dllmc_pool_destroy.argtypes = [C.c_void_p]
         L.dllmc_num_selected.restype = C.c_int32
         L.dllmc_num_selected.argtypes = [C.c_void_p]
         L.dllmc_step.restype = C.c_int
@@ -175,7 +204,10 @@ class CachedDenoiser:
     def __init__(self, *, n_layers: int, d_model: int, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, d_ffn: int, batch: int, dtype: str,
                  weights: Sequence[Dict[str, torch.Tensor]], L_p: int, L_r: int, rho: float,
-                 K_p: int, K_r: int, rms_eps: float = 1e-5, rope_theta: float = 10000.0):
+                 K_p: int, K_r: int, rms_eps: float = 1e-5, rope_theta: float = 10000.0,
+                 paging: Optional[Dict] = None):
+        """paging: None for the flat cache layout, else dict(page_rows, pool_pages, page_table
+        [B][pages per sequence] of ints[, pool: uint8 device tensor shared between contexts])."""
         self._h = None
         L = lib()
         code, tdt = _DTYPES[dtype]
@@ -194,17 +226,43 @@ class CachedDenoiser:
                 if not (t.is_cuda and t.is_contiguous() and t.dtype == tdt):
                     raise DllmcError(f"layer {l} {name}: need a contiguous {tdt} device tensor")
                 setattr(arr[l], name, t.data_ptr())
-        nbytes = L.dllmc_workspace_bytes(C.byref(self.model), L_p, L_r)
-        if nbytes == 0:
-            raise DllmcError("dllmc_workspace_bytes: invalid model description")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         self.stream = _stream_handle()
         h = C.c_void_p()
-        _check(L.dllmc_create(C.byref(h), C.byref(self.model), arr, L_p, L_r, rho, K_p, K_r,
-                              self.workspace.data_ptr(), nbytes, self.stream), "dllmc_create")
+        self.paging = None
+        if paging is None:
+            nbytes = L.dllmc_workspace_bytes(C.byref(self.model), L_p, L_r)
+            if nbytes == 0:
+                raise DllmcError("dllmc_workspace_bytes: invalid model description")
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            _check(L.dllmc_create(C.byref(h), C.byref(self.model), arr, L_p, L_r, rho, K_p, K_r,
+                                  self.workspace.data_ptr(), nbytes, self.stream), "dllmc_create")
+        else:
+            table = self._table(paging["page_table"])
+            pool = paging.get("pool")
+            self._pool = pool   # keep a shared pool alive
+            pg = dllmc_paging(int(paging["page_rows"]), int(paging["pool_pages"]), table,
+                              None if pool is None else pool.data_ptr(),
+                              0 if pool is None else pool.numel() * pool.element_size())
+            nbytes = L.dllmc_workspace_bytes_paged(C.byref(self.model), L_p, L_r, C.byref(pg))
+            if nbytes == 0:
+                raise DllmcError("dllmc_workspace_bytes_paged: invalid model or paging description")
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            _check(L.dllmc_create_paged(C.byref(h), C.byref(self.model), arr, L_p, L_r, rho, K_p, K_r,
+                                        C.byref(pg), self.workspace.data_ptr(), nbytes, self.stream),
+                   "dllmc_create_paged")
+            self.paging = dict(paging)
         self._h = h
         self.num_selected = L.dllmc_num_selected(h)
         self.sel_idx = torch.full((n_layers, batch, L_r), -1, dtype=torch.int32, device="cuda")
+
+    @staticmethod
+    def _table(page_table):
+        flat = [int(p) for row in page_table for p in row]
+        return (C.c_int32 * len(flat))(*flat)
+
+    def set_page_table(self, page_table) -> None:
+        """New page table for a paged context; the next step must be step 0."""
+        _check(lib().dllmc_set_page_table(self._h, self._table(page_table)), "dllmc_set_page_table")
 
     def step(self, hidden_in: torch.Tensor, step_idx: int, hidden_out: Optional[torch.Tensor] = None):
         """Enqueue one denoising step; returns (hidden_out, n_sel).  self.sel_idx[:, :, :n_sel]
@@ -267,6 +325,44 @@ class CachedDenoiser:
         if self._h is not None:
             h, self._h = self._h, None
             _check(lib().dllmc_destroy(h), "dllmc_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def pool_bytes(model: dllmc_model, page_rows: int, pool_pages: int) -> int:
+    return lib().dllmc_pool_bytes(C.byref(model), page_rows, pool_pages)
+
+
+class PagePool:
+    """dllmc_pool_*: host-side allocator of page ids."""
+
+    def __init__(self, pool_pages: int):
+        self._h = None
+        h = C.c_void_p()
+        _check(lib().dllmc_pool_create(C.byref(h), pool_pages), "dllmc_pool_create")
+        self._h = h
+
+    @property
+    def available(self) -> int:
+        return lib().dllmc_pool_available(self._h)
+
+    def alloc(self, count: int) -> List[int]:
+        ids = (C.c_int32 * max(count, 1))()
+        _check(lib().dllmc_pool_alloc(self._h, count, ids), "dllmc_pool_alloc")
+        return list(ids[:count])
+
+    def free(self, ids: Sequence[int]) -> None:
+        arr = (C.c_int32 * max(len(ids), 1))(*[int(i) for i in ids])
+        _check(lib().dllmc_pool_free(self._h, arr, len(ids)), "dllmc_pool_free")
+
+    def close(self) -> None:
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib().dllmc_pool_destroy(h), "dllmc_pool_destroy")
 
     def __del__(self):
         try:

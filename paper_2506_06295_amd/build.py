@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdllmc.so")
-SOURCES = ("kernels_gemm.hip", "kernels_row.hip", "kernels_select.hip", "kernels_attn.hip", "kernels_gen.hip", "kernels_probe.hip", "kernels_fused.hip",
+SOURCES = ("kernels_gemm.hip", "kernels_row.hip", "kernels_select.hip", "kernels_attn.hip", "kernels_gen.hip", "kernels_probe.hip", "kernels_fused.hip", "page_pool.cpp",
            "dllmc_api.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -20,7 +20,7 @@ def build(verbose: bool = False) -> str:
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
         cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

@@ -106,6 +106,34 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // dispatch their slice count to a compile-time constant in 1 .. kMaxSlices
 constexpr int kMaxSlices = 8;
 int gemm_max_slices();
+// Kernel choice and slice planning knobs of the matrix products.  Every context owns a copy (taken
+// from the process default when it is created); the launchers use the copy of the context whose
+// call is running on this thread (TuningScope), the process default otherwise.
+struct GemmTuning {
+  int nw = 8;          // wavefronts per workgroup (4 or 8) of the single-matrix kernel
+  int nw_dual = 106;   // fused gate/up kernel: 6 wavefronts in two groups over the contraction
+                       // range (+100), i.e. 48 columns of each matrix per workgroup: the
+                       // narrowest tile that still amortises the activation tile measured
+                       // fastest at both FFN widths (12288: one workgroup per CU)
+  int force_s = 0;     // > 0: number of slices of the contraction index
+  int target_wg = 256; // workgroups the automatic slice count aims for
+  int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
+  int tall_max_m = 128;     // most rows the streaming kernel covers with one workgroup tile:
+                            // 65..128 rows run with 128 rows per workgroup when it is >= 128
+                            // (weights streamed once instead of once per 64-row tile); from
+                            // 256 on, launches of tile_min_m..tall_max_m rows use 256 rows per
+                            // workgroup instead of the 128 x 128 tiles (slower where measured)
+  int tile_min_m = 192;     // activation rows from which the 128 x 128 LDS-direct kernel is used
+                            // (off by default: the streaming kernel is faster at the sizes measured)
+};
+GemmTuning gemm_default_tuning();
+struct TuningScope {
+  const GemmTuning* prev;
+  explicit TuningScope(const GemmTuning* t);
+  ~TuningScope();
+  TuningScope(const TuningScope&) = delete;
+  TuningScope& operator=(const TuningScope&) = delete;
+};
 // slices launch_gemm would use for 16-byte aligned operands (0: capacity too small); host only
 int gemm_plan_slices(int dtype, int M, int N, int N0, int K, size_t c_capacity);
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg);
@@ -129,6 +157,13 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
 // out[i][:] = sum_s c_part[s][i][:]
 void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, hipStream_t st);
 
+// Paged cache layout: wherever a launcher takes `rmap` (device int32, one entry per logical row
+// b * n + position, or nullptr for the flat layout), logical row r of a cache tensor lives in row
+// rmap[r] of that tensor's storage.
+// out[r][:] = cache[rmap[r]][:] for r < rows
+void launch_gather_rows(int dtype, const void* cache, const int* rmap, int rows, int width,
+                        void* out, hipStream_t st);
+
 struct RowKernelArgs {
   int dtype;
   int n;            // rows per sequence (L_p + L_r)
@@ -148,12 +183,12 @@ void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int*
 // to v_stage[i] instead when v_stage != nullptr (selected-only update, see launch_scatter_v).
 void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, int first, int per_seq,
                        int M, int d_kv, void* v_cache, float* score, int metric, void* v_stage,
-                       hipStream_t st);
+                       hipStream_t st, const int* rmap = nullptr);
 // v_cache[row] = v_stage[(row / n) * carried_per_seq + row % n - first] for the response rows
 // among rows_R[0..M_R)
 void launch_scatter_v(const RowKernelArgs& a, const int* rows_R, int M_R, int first,
                       int carried_per_seq, int d_kv, const void* v_stage, void* v_cache,
-                      hipStream_t st);
+                      hipStream_t st, const int* rmap = nullptr);
 // score[b][j] = 24-bit uniform in [0, 1) keyed by (seed, step, layer, b, j)
 void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, float* out,
                           hipStream_t st);
@@ -165,12 +200,12 @@ void launch_random_scores(uint32_t seed, int step, int layer, int B, int L, floa
 // Values of the selected rows and k_cache is the V cache).
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                         int d_q, int d_kv, int d_h, const float2* rope_tab, void* q_out,
-                        void* k_cache, bool rope_second, hipStream_t st);
+                        void* k_cache, bool rope_second, hipStream_t st, const int* rmap = nullptr);
 // K finalize (K-verify): like launch_v_finalize on the Key projection, with RoPE at the row's
 // position before rounding, scoring and the cache write.
 void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                        int d_kv, int d_h, const float2* rope_tab, void* k_cache, float* score,
-                       int metric, void* k_stage, hipStream_t st);
+                       int metric, void* k_stage, hipStream_t st, const int* rmap = nullptr);
 
 // Output-projection finalize over the recomputed rows: for ci < M_R: row = rows_R[ci];
 // attn_cache[row] = T(sum_s c_part[s][ci][:]) (c_part slices hold M_R rows);
@@ -178,7 +213,7 @@ void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const
 // not recomputed get their x[row] += attn_cache[row] in launch_down_finalize.
 void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows_R,
                        int M_R, void* attn_cache, float* x, const void* gain, void* g_out,
-                       hipStream_t st);
+                       hipStream_t st, const int* rmap = nullptr);
 
 // SwiGLU: u[i][j] = T(silu(c[i][j]) * c[i][m + j]) with c = sum_s c_part[s] of width 2m.
 void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st);
@@ -192,7 +227,8 @@ void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u,
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
                           int first, int per_seq, int Mc, const int* inv, const void* attn_cache,
                           void* ffn_cache, float* x, const void* next_gain, void* h,
-                          void* hidden_out, void* prompt_out, hipStream_t st);
+                          void* hidden_out, void* prompt_out, hipStream_t st,
+                          const int* rmap = nullptr);
 
 // hidden_out[b][t] = prompt_out[b][t] for all prompt rows
 void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, void* hidden_out,
@@ -221,7 +257,7 @@ size_t vverify_part_floats(int N, size_t scored_rows);
 int vverify_col_tiles(int N);
 void launch_vverify_fused(const void* A, int lda, int M, int first, int per_seq, int n, int L_p,
                           const void* W, int N, int K, void* v_cache, float* part, int part_stride,
-                          int metric, hipStream_t st);
+                          int metric, hipStream_t st, const int* rmap = nullptr);
 // score[i] = cosine (metric 0) or minus distance (metric 1) from the tile sums, i < count
 void launch_scores_from_part(const float* part, int n_ct, int count, int metric, float* score,
                              hipStream_t st);
@@ -232,9 +268,10 @@ void launch_scores_from_part(const float* part, int n_ct, int count, int metric,
 bool attention_supported(int dtype, int d_h, int n);
 // scratch (may be null): attention_scratch_floats() floats for the split-key partial results.
 size_t attention_scratch_floats();
+// rmap (paged layout): key row j of sequence b is row rmap[b * n + j] of k_cache / v_cache.
 void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cache,
                       const void* v_cache, int n, int H_q, int H_kv, int d_h, void* out,
-                      float* scratch, hipStream_t st);
+                      float* scratch, hipStream_t st, const int* rmap = nullptr);
 
 // Row lists: for b < B, t < count: ci = b*per_seq + off + t, row = b*n + first + t;
 // rows[ci] = row (if rows), inv[row] = ci (if inv).

@@ -9,12 +9,13 @@
 
 #include "../../include/dllmc.h"
 #include "common.hpp"
+#include "paging_host.hpp"
 
 using namespace dllmc;
 
 namespace {
 
-int g_last_hip_error = 0;
+thread_local int g_last_hip_error = 0;
 
 inline int hip_fail(hipError_t e) {
   g_last_hip_error = static_cast<int>(e);
@@ -49,25 +50,33 @@ struct Layout {
   size_t cws_floats;  // capacity of the GEMM slice buffer
   size_t cache_k, cache_v, cache_ao, cache_fo;  // per-layer strides inside their regions
   size_t off_k, off_v, off_ao, off_fo, off_prompt_out, off_x, off_h, off_q, off_a, off_g, off_u,
-      off_cws, off_attn, off_scores, off_part, off_carried, off_rows, off_inv, off_rope, total;
+      off_cws, off_attn, off_scores, off_part, off_carried, off_rows, off_inv, off_rope, off_rmap,
+      pool_total, total;
 };
 
-Layout make_layout(const dllmc_model& m, int L_p, int L_r) {
+// cache_rows: rows of a layer's cache tensors (B * n flat, pool_pages * page_rows paged);
+// caches_inside: whether the workspace holds them (false: a caller-owned pool does).
+Layout make_layout(const dllmc_model& m, int L_p, int L_r, size_t cache_rows = 0,
+                   bool caches_inside = true, bool paged = false) {
   Layout L{};
   const size_t esz = m.dtype == DLLMC_BF16 ? 2 : 4;
   const size_t B = m.batch, n = static_cast<size_t>(L_p) + L_r, T = m.n_layers;
   const size_t d = m.d_model, d_q = static_cast<size_t>(m.n_q_heads) * m.head_dim,
                d_kv = static_cast<size_t>(m.n_kv_heads) * m.head_dim, mf = m.d_ffn;
   const size_t rows = B * n;
+  if (cache_rows == 0) cache_rows = rows;
   L.esz = esz;
-  L.cache_k = L.cache_v = align_up(rows * d_kv * esz, 256);
-  L.cache_ao = L.cache_fo = align_up(rows * d * esz, 256);
+  L.cache_k = L.cache_v = align_up(cache_rows * d_kv * esz, 256);
+  L.cache_ao = L.cache_fo = align_up(cache_rows * d * esz, 256);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o += align_up(bytes, 256); return r; };
   L.off_k = take(L.cache_k * T);
   L.off_v = take(L.cache_v * T);
   L.off_ao = take(L.cache_ao * T);
   L.off_fo = take(L.cache_fo * T);
+  L.pool_total = o;
+  if (!caches_inside) o = 0;  // the four regions above are offsets into the caller's pool
+  L.off_rmap = paged ? take(rows * sizeof(int)) : 0;
   L.off_prompt_out = take(B * L_p * d * esz);
   L.off_x = take(rows * d * sizeof(float));
   L.off_h = take(rows * d * esz);
@@ -107,7 +116,11 @@ struct dllmc_ctx {
   int last_step;
   Layout lay;
   char* ws;
+  char* cache_base;          // where the four cache regions start: the workspace or a caller's pool
   bool have_scores;
+  // paged layout (page_rows == 0: flat)
+  int page_rows = 0, pool_pages = 0;
+  const int* rmap = nullptr; // device: cache row of every logical row b * n + position
   // variants of the paper's ablations (dllmc_set_policy); defaults are the paper's method
   int metric = 0;          // 0 cosine, 1 minus L2 distance
   bool source_k = false;   // K-verify: Keys are scored and overwritten, Values follow the selection
@@ -115,6 +128,7 @@ struct dllmc_ctx {
   bool v_selected_only = false;
   uint32_t seed = 0;
   std::vector<int> k_layer;  // rows recomputed per sequence on adaptive steps, per layer
+  GemmTuning tune;           // kernel-choice knobs, copied from the process default at creation
 
   // optional per-kernel timing with HIP events on the context's stream
   bool profiling = false;
@@ -135,10 +149,10 @@ struct dllmc_ctx {
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
   void* cache(int which, int layer) const {
     switch (which) {
-      case 0: return ws + lay.off_k + lay.cache_k * layer;
-      case 1: return ws + lay.off_v + lay.cache_v * layer;
-      case 2: return ws + lay.off_ao + lay.cache_ao * layer;
-      default: return ws + lay.off_fo + lay.cache_fo * layer;
+      case 0: return cache_base + lay.off_k + lay.cache_k * layer;
+      case 1: return cache_base + lay.off_v + lay.cache_v * layer;
+      case 2: return cache_base + lay.off_ao + lay.cache_ao * layer;
+      default: return cache_base + lay.off_fo + lay.cache_fo * layer;
     }
   }
 };
@@ -166,14 +180,25 @@ struct Timed {
 
 extern "C" {
 
-size_t dllmc_workspace_bytes(const dllmc_model* model, int32_t L_p, int32_t L_r) {
-  if (!model_ok(model, L_p, L_r)) return 0;
-  return make_layout(*model, L_p, L_r).total;
+}  // extern "C"
+
+namespace {
+
+bool paging_shape_ok(const dllmc_model* m, const dllmc_paging* pg) {
+  if (!pg || pg->page_rows < 1 || pg->pool_pages < 1) return false;
+  const long long rows = static_cast<long long>(pg->page_rows) * pg->pool_pages;
+  return m && rows <= (1ll << 30);
 }
 
-int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
-                 int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r, void* workspace,
-                 size_t workspace_bytes, void* hip_stream) {
+Layout layout_for(const dllmc_model& m, int L_p, int L_r, const dllmc_paging* pg) {
+  if (!pg) return make_layout(m, L_p, L_r);
+  return make_layout(m, L_p, L_r, static_cast<size_t>(pg->page_rows) * pg->pool_pages,
+                     pg->pool == nullptr, true);
+}
+
+int create_impl(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r,
+                const dllmc_paging* pg, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!out) return DLLMC_EINVAL;
   *out = nullptr;
   if (!model_ok(model, L_p, L_r) || !layers || !workspace) return DLLMC_EINVAL;
@@ -186,8 +211,16 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
     for (const void* p : ps)
       if (!p || (reinterpret_cast<uintptr_t>(p) & 15u)) return DLLMC_EINVAL;
   }
-  const Layout lay = make_layout(*model, L_p, L_r);
+  std::vector<int> row_map;
+  if (pg) {
+    if (!paging_shape_ok(model, pg) || !pg->page_table) return DLLMC_EINVAL;
+    if (pg->pool && (reinterpret_cast<uintptr_t>(pg->pool) & 255u)) return DLLMC_EINVAL;
+    row_map = build_row_map(model->batch, L_p + L_r, pg->page_rows, pg->pool_pages, pg->page_table);
+    if (row_map.empty()) return DLLMC_EINVAL;
+  }
+  const Layout lay = layout_for(*model, L_p, L_r, pg);
   if (workspace_bytes < lay.total) return DLLMC_ENOMEM;
+  if (pg && pg->pool && pg->pool_bytes < lay.pool_total) return DLLMC_ENOMEM;
 
   dllmc_ctx* c = new (std::nothrow) dllmc_ctx();
   if (!c) return DLLMC_ENOMEM;
@@ -203,11 +236,18 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
   c->k_sel = static_cast<int>(std::floor(static_cast<double>(rho) * L_r + 1e-6));
   if (c->k_sel > L_r) c->k_sel = L_r;
   c->k_layer.assign(model->n_layers, c->k_sel);
+  c->tune = gemm_default_tuning();
   c->st = static_cast<hipStream_t>(hip_stream);
   c->last_step = -1;
   c->lay = lay;
   c->ws = static_cast<char*>(workspace);
+  c->cache_base = (pg && pg->pool) ? static_cast<char*>(pg->pool) : c->ws;
   c->have_scores = false;
+  if (pg) {
+    c->page_rows = pg->page_rows;
+    c->pool_pages = pg->pool_pages;
+    c->rmap = c->at<int>(lay.off_rmap);
+  }
 
   // RoPE table in double on the host: (cos, sin)(pos * theta^(-2t/d_h))
   const int half = model->head_dim / 2;
@@ -222,12 +262,65 @@ int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_we
     }
   hipError_t e = hipMemcpyAsync(c->ws + lay.off_rope, tab.data(), tab.size() * sizeof(float2),
                                 hipMemcpyHostToDevice, c->st);
+  if (e == hipSuccess && pg)
+    e = hipMemcpyAsync(c->ws + lay.off_rmap, row_map.data(), row_map.size() * sizeof(int),
+                       hipMemcpyHostToDevice, c->st);
   if (e == hipSuccess) e = hipStreamSynchronize(c->st);
   if (e != hipSuccess) {
     delete c;
     return hip_fail(e);
   }
   *out = c;
+  return DLLMC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dllmc_workspace_bytes(const dllmc_model* model, int32_t L_p, int32_t L_r) {
+  if (!model_ok(model, L_p, L_r)) return 0;
+  return make_layout(*model, L_p, L_r).total;
+}
+
+size_t dllmc_pool_bytes(const dllmc_model* model, int32_t page_rows, int32_t pool_pages) {
+  dllmc_paging pg{page_rows, pool_pages, nullptr, nullptr, 0};
+  if (!model_ok(model, 0, 1) || !paging_shape_ok(model, &pg)) return 0;
+  return make_layout(*model, 0, 1, static_cast<size_t>(page_rows) * pool_pages, false, true).pool_total;
+}
+
+size_t dllmc_workspace_bytes_paged(const dllmc_model* model, int32_t L_p, int32_t L_r,
+                                   const dllmc_paging* paging) {
+  if (!model_ok(model, L_p, L_r) || !paging_shape_ok(model, paging)) return 0;
+  return layout_for(*model, L_p, L_r, paging).total;
+}
+
+int dllmc_create(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                 int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  return create_impl(out, model, layers, L_p, L_r, rho, K_p, K_r, nullptr, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+int dllmc_create_paged(dllmc_ctx** out, const dllmc_model* model, const dllmc_layer_weights* layers,
+                       int32_t L_p, int32_t L_r, float rho, int32_t K_p, int32_t K_r,
+                       const dllmc_paging* paging, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  if (!paging) return DLLMC_EINVAL;
+  return create_impl(out, model, layers, L_p, L_r, rho, K_p, K_r, paging, workspace, workspace_bytes,
+                     hip_stream);
+}
+
+int dllmc_set_page_table(dllmc_ctx* c, const int32_t* page_table) {
+  if (!c || !page_table || c->page_rows == 0) return DLLMC_EINVAL;
+  const std::vector<int> row_map = build_row_map(c->m.batch, c->n, c->page_rows, c->pool_pages, page_table);
+  if (row_map.empty()) return DLLMC_EINVAL;
+  HIP_TRY(hipStreamSynchronize(c->st));  // nothing in flight may still read the old map
+  HIP_TRY(hipMemcpyAsync(c->ws + c->lay.off_rmap, row_map.data(), row_map.size() * sizeof(int),
+                         hipMemcpyHostToDevice, c->st));
+  HIP_TRY(hipStreamSynchronize(c->st));
+  c->last_step = -1;  // the caches are void: a full refresh (step 0) comes next
+  c->have_scores = false;
   return DLLMC_OK;
 }
 
@@ -272,6 +365,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   if (!c || !hidden_in || !hidden_out || step_idx < 0) return DLLMC_EINVAL;
   if (step_idx != 0 && (c->last_step < 0 || step_idx <= c->last_step)) return DLLMC_ESTATE;
   (void)hipGetLastError();  // do not inherit a stale error
+  const TuningScope tuning(&c->tune);
 
   const dllmc_model& m = c->m;
   const int B = m.batch, n = c->n, L_p = c->L_p, L_r = c->L_r, T = m.n_layers;
@@ -310,6 +404,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
   float* part = c->at<float>(c->lay.off_part);
   void* prompt_out = c->ws + c->lay.off_prompt_out;
   const float2* rope_tab = c->at<float2>(c->lay.off_rope);
+  const int* rmap = c->rmap;  // paged layout: cache row of every logical row (nullptr: flat)
 
   c->last_event = nullptr;
   if (c->profiling) {
@@ -370,7 +465,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
               gemm_flops(Mc, d_kv, d));
       gemm_clear_last_stream();
       launch_vverify_fused(h, d, Mc, P ? 0 : L_p, carried_per_seq, n, L_p, w.wv, d_kv, d, Vc,
-                           part_scores ? part : nullptr, B * L_r, c->metric, st);
+                           part_scores ? part : nullptr, B * L_r, c->metric, st, rmap);
     } else {
       Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
       S = launch_gemm(dt, h, d, carried, Mc, ksrc ? w.wk : w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap,
@@ -382,10 +477,10 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       float* sc_out = (Rf || c->random_sel) ? nullptr : sc;
       if (ksrc)
         launch_k_finalize(ra, cws, S, carried, Mc, d_kv, d_h, rope_tab, Tc, sc_out, c->metric,
-                          defer_v ? abuf : nullptr, st);
+                          defer_v ? abuf : nullptr, st, rmap);
       else
         launch_v_finalize(ra, cws, S, P ? 0 : L_p, carried_per_seq, Mc, d_kv, Tc, sc_out, c->metric,
-                          defer_v ? abuf : nullptr, st);
+                          defer_v ? abuf : nullptr, st, rmap);
     }
     if (!Rf) {
       Timed t(c, DLLMC_KC_SELECT, B * (L_r * 4.0 + k_l * 8.0 + L_r * 4.0), 0);
@@ -395,7 +490,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
                     per_seq, sel_off, inv, n, L_p, st, part_scores ? part : nullptr,
                     vverify_col_tiles(d_kv), B * L_r, c->metric);
       if (defer_v)
-        launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Tc, st);
+        launch_scatter_v(ra, rows_R, M_R, P ? 0 : L_p, carried_per_seq, d_kv, abuf, Tc, st, rmap);
     }
     S = 1;
     if (M_R > 0) {
@@ -409,14 +504,14 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       {
         Timed t(c, DLLMC_KC_ROW, M_R * (d_q + d_kv) * (4.0 + esz), 0);
         launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, ksrc ? Vc : Kc,
-                           !ksrc, st);
+                           !ksrc, st, rmap);
       }
       {
         // queries in and out once, every sequence's K and V once per group of query heads
         Timed t(c, DLLMC_KC_ATTENTION, (2.0 * M_R * d_q + 2.0 * B * n * d_kv) * esz,
                 4.0 * M_R * static_cast<double>(n) * d_q);
         launch_attention(dt, qbuf, B, per_seq, Kc, Vc, n, m.n_q_heads, m.n_kv_heads, d_h, abuf,
-                         c->at<float>(c->lay.off_attn), st);
+                         c->at<float>(c->lay.off_attn), st, rmap);
       }
       {
         Timed t(c, DLLMC_KC_GEMM_O, gemm_bytes(M_R, d, d_q), gemm_flops(M_R, d, d_q));
@@ -426,7 +521,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     }
     {
       Timed t(c, DLLMC_KC_ROW, M_R * d * (12.0 + 2.0 * esz), 0);
-      launch_o_finalize(ra, cws, S, rows_R, M_R, c->cache(2, l), x, w.ffn_norm_g, gbuf, st);
+      launch_o_finalize(ra, cws, S, rows_R, M_R, c->cache(2, l), x, w.ffn_norm_g, gbuf, st, rmap);
     }
     if (M_R > 0) {
       bool fused;
@@ -451,7 +546,7 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
       Timed t(c, DLLMC_KC_ROW, Mc * d * (8.0 + 2.0 * esz) + M_R * d * 4.0 + (Mc - M_R) * d * esz, 0);
       launch_down_finalize(ra, cws, S, M_R, P ? 0 : L_p, carried_per_seq, Mc, inv, c->cache(2, l), c->cache(3, l), x,
                            last ? nullptr : c->layers[l + 1].attn_norm_g, h, hidden_out,
-                           (last && P) ? prompt_out : nullptr, st);
+                           (last && P) ? prompt_out : nullptr, st, rmap);
     }
   }
   if (!P) {
@@ -472,6 +567,14 @@ int dllmc_read_cache(dllmc_ctx* c, int32_t layer, int32_t which, void* dst_devic
   const size_t width = which < 2 ? static_cast<size_t>(c->m.n_kv_heads) * c->m.head_dim
                                  : static_cast<size_t>(c->m.d_model);
   const size_t bytes = static_cast<size_t>(c->m.batch) * c->n * width * c->lay.esz;
+  if (c->rmap) {
+    // paged layout: the rows gathered into logical order
+    (void)hipGetLastError();
+    launch_gather_rows(c->m.dtype, c->cache(which, layer), c->rmap, c->m.batch * c->n,
+                       static_cast<int>(width), dst_device, c->st);
+    HIP_TRY(hipGetLastError());
+    return DLLMC_OK;
+  }
   HIP_TRY(hipMemcpyAsync(dst_device, c->cache(which, layer), bytes, hipMemcpyDeviceToDevice, c->st));
   return DLLMC_OK;
 }
@@ -780,6 +883,7 @@ int dllmc_gen_step(dllmc_gen* g, int32_t* tokens, int32_t step_idx, int32_t* sel
                    int32_t* n_sel, int32_t* n_revealed) {
   if (!g || !tokens || step_idx < 0 || step_idx >= g->g.steps) return DLLMC_EINVAL;
   dllmc_ctx* c = g->c;
+  const TuningScope tuning(&c->tune);
   const int B = c->m.batch, n = c->n, L_p = c->L_p, L_r = c->L_r, d = c->m.d_model, dt = c->m.dtype;
   hipStream_t st = c->st;
   void* hin = g->ws + g->lay.off_hin;

@@ -29,7 +29,8 @@ template <typename T>
 __global__ __launch_bounds__(64) void k_attn_simple(const T* __restrict__ q, int Mq,
                                                     const T* __restrict__ kc,
                                                     const T* __restrict__ vc, int n, int H_q,
-                                                    int H_kv, int d_h, T* __restrict__ out) {
+                                                    int H_kv, int d_h, T* __restrict__ out,
+                                                    const int* __restrict__ rmap) {
   extern __shared__ float sm[];
   float* qs = sm;        // [d_h]
   float* sc = sm + d_h;  // [n]
@@ -38,14 +39,16 @@ __global__ __launch_bounds__(64) void k_attn_simple(const T* __restrict__ q, int
   const int d_q = H_q * d_h, d_kv = H_kv * d_h;
   const int kv = a / (H_q / H_kv);
   const T* qr = q + (static_cast<size_t>(b) * Mq + i) * d_q + a * d_h;
-  const T* K = kc + static_cast<size_t>(b) * n * d_kv + kv * d_h;
-  const T* V = vc + static_cast<size_t>(b) * n * d_kv + kv * d_h;
+  // row j of this sequence in the cache tensors (the row map's entry in the paged layout)
+  auto crow = [&](int j) { return static_cast<size_t>(rmap ? rmap[b * n + j] : b * n + j); };
+  const T* K = kc + kv * d_h;
+  const T* V = vc + kv * d_h;
   const float scale = 1.0f / sqrtf(static_cast<float>(d_h));
   for (int t = lane; t < d_h; t += 64) qs[t] = ldf(qr + t);
   __syncthreads();
   float mx = -INFINITY;
   for (int j = lane; j < n; j += 64) {
-    const T* kr = K + static_cast<size_t>(j) * d_kv;
+    const T* kr = K + crow(j) * d_kv;
     float acc = 0.f;
     for (int t = 0; t < d_h; ++t) acc = fmaf(qs[t], ldf(kr + t), acc);
     acc *= scale;
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(64) void k_attn_simple(const T* __restrict__ q, int
   T* o = out + (static_cast<size_t>(b) * Mq + i) * d_q + a * d_h;
   for (int t = lane; t < d_h; t += 64) {
     float acc = 0.f;
-    for (int j = 0; j < n; ++j) acc = fmaf(sc[j], ldf(V + static_cast<size_t>(j) * d_kv + t), acc);
+    for (int j = 0; j < n; ++j) acc = fmaf(sc[j], ldf(V + crow(j) * d_kv + t), acc);
     stf(o + t, acc / sum);
   }
 }
@@ -215,7 +218,7 @@ __device__ __forceinline__ void attn_finish(const f32x4 (&o_acc)[8], float m_run
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_attn_mfma(
     const bf16_t* __restrict__ q, int Mq, const bf16_t* __restrict__ kc,
     const bf16_t* __restrict__ vc, int n, int H_q, int H_kv, int KS, bf16_t* __restrict__ out,
-    float* __restrict__ part) {
+    float* __restrict__ part, const int* __restrict__ rmap) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kPreload][kDH * kVtStride];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
@@ -225,8 +228,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
   const int kv = a / (H_q / H_kv);
   const int i0 = blockIdx.x * kQT + wave * 16;  // first query of this wavefront
 
-  const bf16_t* K = kc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
-  const bf16_t* V = vc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
+  // key row j of this sequence: cache row b * n + j, or the row map's entry (paged layout)
+  const bf16_t* K = kc + kv * kDH;
+  const bf16_t* V = vc + kv * kDH;
+  const int seq0 = b * n;
 
   // Q fragments (B operand of S^T = K Q^T): lane (query ln, group lg) holds dims 32c+8lg..+8
   int qi = i0 + ln;
@@ -260,7 +265,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
       for (int sb = 0; sb < 2; ++sb) {
         int kr = blk * 32 + sb * 16 + ln;
         if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
-        const bf16_t* kptr = K + static_cast<size_t>(kr) * d_kv + lg * 8;
+        const size_t cr = static_cast<size_t>(rmap ? rmap[seq0 + kr] : seq0 + kr);
+        const bf16_t* kptr = K + cr * d_kv + lg * 8;
 #pragma unroll
         for (int c = 0; c < 4; ++c) kall[j][sb][c] = *reinterpret_cast<const bf16x8*>(kptr + c * 32);
       }
@@ -268,7 +274,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
       for (int h = 0; h < 2; ++h) {
         int kr = blk * 32 + 2 * kp + h;
         if (kr >= n) kr = n - 1;
-        vall[j][h] = *reinterpret_cast<const uint4*>(V + static_cast<size_t>(kr) * d_kv + ch * 8);
+        const size_t cr = static_cast<size_t>(rmap ? rmap[seq0 + kr] : seq0 + kr);
+        vall[j][h] = *reinterpret_cast<const uint4*>(V + cr * d_kv + ch * 8);
       }
     }
 #pragma unroll
@@ -309,7 +316,8 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
                                                    int H_kv, int KS, bf16_t* __restrict__ out,
-                                                   float* __restrict__ part) {
+                                                   float* __restrict__ part,
+                                                   const int* __restrict__ rmap) {
   // [stage][K tile, V tile][32 keys][16 slots of 16 bytes]
   __shared__ __attribute__((aligned(1024))) uint4 tiles[kWalkStages][2][32 * 16];
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kDH * kVtStrideW];
@@ -321,8 +329,9 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
   const int kv = a / (H_q / H_kv);
   const int i0 = blockIdx.x * kQT + wave * 16;
 
-  const bf16_t* K = kc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
-  const bf16_t* V = vc + static_cast<size_t>(b) * n * d_kv + kv * kDH;
+  const bf16_t* K = kc + kv * kDH;
+  const bf16_t* V = vc + kv * kDH;
+  const int seq0 = b * n;
 
   int qi = i0 + ln;
   if (qi >= Mq) qi = Mq - 1;  // padded queries compute a duplicate that is never stored
@@ -356,12 +365,20 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
       kchunk[j] = (lane % 16) ^ (lkey[j] % 16);
       vchunk[j] = (lane % 16) ^ ((lkey[j] >> 1) % 16);
     }
-    auto issue = [&](int blk, int stage) {
+    // cache rows of this lane's two keys of a block: the rows themselves, or (paged layout) the
+    // row map's entries, looked up one block before the block's loads are issued
+    auto rows_of = [&](int blk, int (&cr)[2]) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         int kr = blk * 32 + lkey[j];
         if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
-        const size_t row = static_cast<size_t>(kr) * d_kv;
+        cr[j] = rmap ? rmap[seq0 + kr] : seq0 + kr;
+      }
+    };
+    auto issue = [&](const int (&cr)[2], int stage) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const size_t row = static_cast<size_t>(cr[j]) * d_kv;
         __builtin_amdgcn_global_load_lds(K + row + kchunk[j] * 8, &tiles[stage][0][(2 * wave + j) * 64],
                                          16, 0, 0);
         __builtin_amdgcn_global_load_lds(V + row + vchunk[j] * 8, &tiles[stage][1][(2 * wave + j) * 64],
@@ -370,8 +387,13 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
     };
     // blocks past the range repeat the last one (never used): the number of loads in flight
     // stays the same in every iteration
+    int cr_next[2];
 #pragma unroll
-    for (int s = 0; s < kWalkStages - 1; ++s) issue(min(blk0 + s, blk1 - 1), s);
+    for (int s = 0; s < kWalkStages - 1; ++s) {
+      rows_of(min(blk0 + s, blk1 - 1), cr_next);
+      issue(cr_next, s);
+    }
+    rows_of(min(blk0 + kWalkStages - 1, blk1 - 1), cr_next);
 
     // V transposition: thread = (key pair kp, 16-byte chunk vch); it reads the chunk of keys 2kp
     // and 2kp+1 and writes, per dim, one 32-bit word holding both keys.  Consecutive lanes write
@@ -383,12 +405,17 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
     for (int i = 0; i < nb; ++i) {
       const int stage = i % kWalkStages;
       // 4 loads per block and wavefront, kWalkStages - 1 blocks in flight: the oldest has landed
-      __builtin_amdgcn_s_waitcnt(0x0F70 | ((4 * (kWalkStages - 2)) & 15) |
-                                 (((4 * (kWalkStages - 2)) >> 4) << 14));
+      // (paged layout: the two row-map lookups of the block after those are in flight as well)
+      if (rmap) wait_vmcnt<4 * (kWalkStages - 2) + 2>();
+      else wait_vmcnt<4 * (kWalkStages - 2)>();
       // everybody's loads of block i have landed, and everybody is done with block i - 1: its
       // stage and Vt may be overwritten
       __builtin_amdgcn_s_barrier();
-      issue(min(blk0 + i + kWalkStages - 1, blk1 - 1), (i + kWalkStages - 1) % kWalkStages);
+      // The lookups for the block after the one issued now go out first: they are then older
+      // than this block's loads, and waiting for them in the next iteration leaves those in flight.
+      const int cr_use[2] = {cr_next[0], cr_next[1]};
+      rows_of(min(blk0 + i + kWalkStages, blk1 - 1), cr_next);
+      issue(cr_use, (i + kWalkStages - 1) % kWalkStages);
       {
         const uint4 r0 = tiles[stage][1][(2 * kp) * 16 + (vch ^ kp)];
         const uint4 r1 = tiles[stage][1][(2 * kp + 1) * 16 + (vch ^ kp)];
@@ -464,7 +491,7 @@ bool attention_supported(int dtype, int d_h, int n) {
 
 void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cache,
                       const void* v_cache, int n, int H_q, int H_kv, int d_h, void* out,
-                      float* scratch, hipStream_t st) {
+                      float* scratch, hipStream_t st, const int* rmap) {
   if (B <= 0 || Mq <= 0 || n <= 0) return;
   if (dtype == 1 && d_h == kDH) {
     const bf16_t* qq = static_cast<const bf16_t*>(q);
@@ -484,10 +511,10 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     }
     if ((nblk + KS - 1) / KS <= kPreload)
       hipLaunchKernelGGL(k_attn_mfma, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
-                         H_kv, KS, oo, scratch);
+                         H_kv, KS, oo, scratch, rmap);
     else
       hipLaunchKernelGGL(k_attn_walk, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
-                         H_kv, KS, oo, scratch);
+                         H_kv, KS, oo, scratch, rmap);
     if (KS > 8)
       hipLaunchKernelGGL(k_attn_merge<kMaxKeySplit>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS,
                          oo);
@@ -500,12 +527,12 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     hipLaunchKernelGGL(k_attn_simple<bf16_t>, dim3(Mq, H_q, B), dim3(64), lds, st,
                        static_cast<const bf16_t*>(q), Mq, static_cast<const bf16_t*>(k_cache),
                        static_cast<const bf16_t*>(v_cache), n, H_q, H_kv, d_h,
-                       static_cast<bf16_t*>(out));
+                       static_cast<bf16_t*>(out), rmap);
   else
     hipLaunchKernelGGL(k_attn_simple<float>, dim3(Mq, H_q, B), dim3(64), lds, st,
                        static_cast<const float*>(q), Mq, static_cast<const float*>(k_cache),
                        static_cast<const float*>(v_cache), n, H_q, H_kv, d_h,
-                       static_cast<float*>(out));
+                       static_cast<float*>(out), rmap);
 }
 
 }  // namespace dllmc

@@ -44,7 +44,7 @@ template <int KH>
 __global__ __launch_bounds__(256 * KH) void k_vverify_tile(
     const bf16_t* __restrict__ A, int lda, int M, int first, int per_seq, int n, int L_p,
     const bf16_t* __restrict__ W, int N, int K, bf16_t* __restrict__ v_cache,
-    float* __restrict__ part, int part_stride, int metric) {
+    float* __restrict__ part, int part_stride, int metric, const int* __restrict__ rmap) {
   // [group][stage][activation rows, then weight rows][8 slots of 16 bytes]; slot = chunk ^ (row % 8)
   __shared__ __attribute__((aligned(1024))) uint4 lds_all[KH][kVStages][(kVT + kVT) * 8];
   __shared__ __attribute__((aligned(16))) bf16_t Vn[kVT * kVnStride];
@@ -79,7 +79,9 @@ __global__ __launch_bounds__(256 * KH) void k_vverify_tile(
     }
   }
   const bool scored = evalid && part != nullptr && epos >= L_p;
-  bf16_t* vrow = v_cache + static_cast<size_t>(erow) * N + n0 + eq * ECOLS;
+  // paged layout: the cache row that holds logical row erow
+  const size_t crow = static_cast<size_t>((rmap != nullptr && evalid) ? rmap[erow] : erow);
+  bf16_t* vrow = v_cache + crow * N + n0 + eq * ECOLS;
   // the cached values this thread scores against: requested first, they arrive under the loop
   uint4 vo[EV];
 #pragma unroll
@@ -279,18 +281,18 @@ int vverify_col_tiles(int N) { return N / kVT; }
 
 void launch_vverify_fused(const void* A, int lda, int M, int first, int per_seq, int n, int L_p,
                           const void* W, int N, int K, void* v_cache, float* part, int part_stride,
-                          int metric, hipStream_t st) {
+                          int metric, hipStream_t st, const int* rmap) {
   if (M <= 0) return;
   const dim3 grid(N / kVT, (M + kVT - 1) / kVT);
   // two wavefront groups when the halves of the contraction range are whole steps
   if ((K / kVK) % 2 == 0 && K / kVK >= 8)
     hipLaunchKernelGGL(k_vverify_tile<2>, grid, dim3(512), 0, st, static_cast<const bf16_t*>(A), lda,
                        M, first, per_seq, n, L_p, static_cast<const bf16_t*>(W), N, K,
-                       static_cast<bf16_t*>(v_cache), part, part_stride, metric);
+                       static_cast<bf16_t*>(v_cache), part, part_stride, metric, rmap);
   else
     hipLaunchKernelGGL(k_vverify_tile<1>, grid, dim3(256), 0, st, static_cast<const bf16_t*>(A), lda,
                        M, first, per_seq, n, L_p, static_cast<const bf16_t*>(W), N, K,
-                       static_cast<bf16_t*>(v_cache), part, part_stride, metric);
+                       static_cast<bf16_t*>(v_cache), part, part_stride, metric, rmap);
 }
 
 void launch_scores_from_part(const float* part, int n_ct, int count, int metric, float* score,

@@ -18,6 +18,8 @@
 //                      launches with hundreds of activation rows; the same body with paired
 //                      gate/up column blocks and SwiGLU in the epilogue (k_gemm_*_swiglu,
 //                      k_gemm_tall_swiglu: 256 x 96 for up to 256 rows).
+#include <mutex>
+
 #include "common.hpp"
 
 namespace dllmc {
@@ -554,23 +556,20 @@ void launch_reduce_slices(const float* c_part, int S, int M, int N, float* out, 
 
 // ------------------------------------------------------------------------------------
 namespace {
-struct GemmTuning {
-  int nw = 8;          // wavefronts per workgroup (4 or 8) of the single-matrix kernel
-  int nw_dual = 106;   // fused gate/up kernel: 6 wavefronts in two groups over the contraction
-                       // range (+100), i.e. 48 columns of each matrix per workgroup: the
-                       // narrowest tile that still amortises the activation tile measured
-                       // fastest at both FFN widths (12288: one workgroup per CU)
-  int force_s = 0;     // > 0: number of slices of the contraction index
-  int target_wg = 256; // workgroups the automatic slice count aims for
-  int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
-  int tall_max_m = 128;     // most rows the streaming kernel covers with one workgroup tile:
-                            // 65..128 rows run with 128 rows per workgroup when it is >= 128
-                            // (weights streamed once instead of once per 64-row tile); from
-                            // 256 on, launches of tile_min_m..tall_max_m rows use 256 rows per
-                            // workgroup instead of the 128 x 128 tiles (slower where measured)
-  int tile_min_m = 192;     // activation rows from which the 128 x 128 LDS-direct kernel is used
-                            // (off by default: the streaming kernel is faster at the sizes measured)
-} g_tune;
+// The process default (guarded by a mutex: contexts copy it at creation, dllmc_set_gemm_tuning
+// writes it) and the settings in force on this thread: a context's own copy while one of its
+// calls runs (TuningScope), else a snapshot of the default taken by the calling launcher.
+GemmTuning g_default_tune;
+std::mutex g_tune_mu;
+thread_local const GemmTuning* t_scope = nullptr;
+thread_local GemmTuning t_snapshot;
+const GemmTuning& tune() {
+  if (t_scope) return *t_scope;
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  t_snapshot = g_default_tune;
+  return t_snapshot;
+}
+#define g_tune (tune())
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -592,17 +591,27 @@ static thread_local bool t_last_stream = false;
 bool gemm_last_was_stream() { return t_last_stream; }
 void gemm_clear_last_stream() { t_last_stream = false; }
 
-void gemm_set_tile_min_m(int m) { if (m > 0) g_tune.tile_min_m = m; }
-void gemm_set_tall_max_m(int m) { if (m >= 0) g_tune.tall_max_m = m; }
-void gemm_set_fat_min_m(int m) { if (m > 0) g_tune.fat_min_m = m; }
+#undef g_tune
+GemmTuning gemm_default_tuning() {
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  return g_default_tune;
+}
+TuningScope::TuningScope(const GemmTuning* t) : prev(t_scope) { t_scope = t; }
+TuningScope::~TuningScope() { t_scope = prev; }
+
+void gemm_set_tile_min_m(int m) { std::lock_guard<std::mutex> lock(g_tune_mu); if (m > 0) g_default_tune.tile_min_m = m; }
+void gemm_set_tall_max_m(int m) { std::lock_guard<std::mutex> lock(g_tune_mu); if (m >= 0) g_default_tune.tall_max_m = m; }
+void gemm_set_fat_min_m(int m) { std::lock_guard<std::mutex> lock(g_tune_mu); if (m > 0) g_default_tune.fat_min_m = m; }
 
 void gemm_set_tuning(int nw, int nw_dual, int force_s, int target_wg) {
-  if (nw == 4 || nw == 8) g_tune.nw = nw;
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  if (nw == 4 || nw == 8) g_default_tune.nw = nw;
   if (nw_dual == 4 || nw_dual == 8 || nw_dual == 104 || nw_dual == 106 || nw_dual == 108)
-    g_tune.nw_dual = nw_dual;
-  if (force_s >= 0) g_tune.force_s = force_s;
-  if (target_wg > 0) g_tune.target_wg = target_wg;
+    g_default_tune.nw_dual = nw_dual;
+  if (force_s >= 0) g_default_tune.force_s = force_s;
+  if (target_wg > 0) g_default_tune.target_wg = target_wg;
 }
+#define g_tune (tune())
 
 // Which kernel, how many slices of the contraction index and how long a slice: pure host logic.
 struct GemmPlan {
@@ -840,5 +849,7 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
 #undef DLLMC_GD
   return true;
 }
+
+#undef g_tune
 
 }  // namespace dllmc

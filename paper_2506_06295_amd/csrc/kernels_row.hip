@@ -19,6 +19,12 @@ constexpr int kRegVecs = 4;  // vectors of a row a thread keeps in registers (ro
 
 template <int V> struct Vec { float v[V]; };
 
+// Row of a cache tensor that holds logical row `row`: the row itself in the flat layout, the
+// row map's entry in the paged one.
+__device__ __forceinline__ size_t cache_row(const int* __restrict__ rmap, int row) {
+  return static_cast<size_t>(rmap ? rmap[row] : row);
+}
+
 template <int V> __device__ __forceinline__ Vec<V> ld_f32(const float* p);
 template <> __device__ __forceinline__ Vec<1> ld_f32<1>(const float* p) { return {{*p}}; }
 template <> __device__ __forceinline__ Vec<4> ld_f32<4>(const float* p) {
@@ -202,13 +208,14 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
                                                          int per_seq, int d_kv, int n, int L_p,
                                                          T* __restrict__ v_cache,
                                                          float* __restrict__ score, int metric,
-                                                         T* __restrict__ v_stage) {
+                                                         T* __restrict__ v_stage,
+                                                         const int* __restrict__ rmap) {
   __shared__ float red[kNW];
   const int i = blockIdx.x;
   // carried rows are positions first .. first + per_seq - 1 of every sequence (per_seq = 0: row i):
   // computed, not looked up, so the cached row's loads go out together with the slices'
   const int row = per_seq > 0 ? (i / per_seq) * n + first + i % per_seq : i;
-  T* vc = v_cache + static_cast<size_t>(row) * d_kv;
+  T* vc = v_cache + cache_row(rmap, row) * d_kv;
   const int pos = row % n;
   const bool scored = (score != nullptr) && (pos >= L_p);
   // selected-only update: response rows are parked in v_stage[i] until the selection is known
@@ -269,7 +276,7 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
                                                     int d_kv, int d_h,
                                                     const float2* __restrict__ rope_tab,
                                                     T* __restrict__ q_out, T* __restrict__ k_cache,
-                                                    int rope_second) {
+                                                    int rope_second, const int* __restrict__ rmap) {
   const int i = blockIdx.x, head = blockIdx.y;
   const int row = rows[i];
   const int pos = row % n;
@@ -278,7 +285,7 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
   const float2* tab = rope_tab + static_cast<size_t>(pos) * half;
   const int c0 = head * d_h;  // first column of the head inside [Q | K]
   T* dst = c0 < d_q ? q_out + static_cast<size_t>(i) * d_q + c0
-                    : k_cache + static_cast<size_t>(row) * d_kv + (c0 - d_q);
+                    : k_cache + cache_row(rmap, row) * d_kv + (c0 - d_q);
   for (int t = threadIdx.x; t < half; t += 64) {
     const size_t off = static_cast<size_t>(i) * width + c0 + t;
     float2 ab;
@@ -301,13 +308,14 @@ __global__ __launch_bounds__(kThreads) void k_k_finalize(const float* __restrict
                                                          const float2* __restrict__ rope_tab,
                                                          T* __restrict__ k_cache,
                                                          float* __restrict__ score, int metric,
-                                                         T* __restrict__ k_stage) {
+                                                         T* __restrict__ k_stage,
+                                                         const int* __restrict__ rmap) {
   __shared__ float red[kNW];
   const int i = blockIdx.x;
   const int row = rows ? rows[i] : i;
   const int pos = row % n;
   const int half = d_h / 2;
-  T* kc = k_cache + static_cast<size_t>(row) * d_kv;
+  T* kc = k_cache + cache_row(rmap, row) * d_kv;
   T* kdst = (k_stage != nullptr && pos >= L_p) ? k_stage + static_cast<size_t>(i) * d_kv : kc;
   const bool scored = (score != nullptr) && (pos >= L_p);
   const float2* tab = rope_tab + static_cast<size_t>(pos) * half;
@@ -354,11 +362,12 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
                                                          float eps, T* __restrict__ attn_cache,
                                                          float* __restrict__ x,
                                                          const T* __restrict__ gain,
-                                                         T* __restrict__ g_out) {
+                                                         T* __restrict__ g_out,
+                                                         const int* __restrict__ rmap) {
   __shared__ float red[kNW];
   const int ci = blockIdx.x;
   const int row = rows_R[ci];
-  T* ac = attn_cache + static_cast<size_t>(row) * d;
+  T* ac = attn_cache + cache_row(rmap, row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
@@ -399,8 +408,9 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c_part, int S,
                                                      size_t slice_stride, int m,
                                                      T* __restrict__ u) {
-  const int i = blockIdx.y;
-  const int j = blockIdx.x * kThreads + threadIdx.x;
+  // rows on grid.x (up to 2^31 - 1 of them), column blocks on grid.y
+  const int i = blockIdx.x;
+  const int j = blockIdx.y * kThreads + threadIdx.x;
   if (j >= m) return;
   const size_t off = static_cast<size_t>(i) * 2 * m + j;
   float2 gu;
@@ -415,14 +425,15 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
     const int* __restrict__ inv, int d, int n, int L_p, float eps,
     const T* __restrict__ attn_cache, T* __restrict__ ffn_cache, float* __restrict__ x,
     const T* __restrict__ next_gain, T* __restrict__ h, T* __restrict__ hidden_out,
-    T* __restrict__ prompt_out) {
+    T* __restrict__ prompt_out, const int* __restrict__ rmap) {
   __shared__ float red[kNW];
   // carried rows are positions first .. first + per_seq - 1 of every sequence: computed, so that
   // the row's loads do not wait for a list entry
   const int i = blockIdx.x;
   const int row = (i / per_seq) * n + first + i % per_seq;
-  T* fc = ffn_cache + static_cast<size_t>(row) * d;
-  const T* ac = attn_cache + static_cast<size_t>(row) * d;
+  const size_t crow = cache_row(rmap, row);
+  T* fc = ffn_cache + crow * d;
+  const T* ac = attn_cache + crow * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
@@ -492,13 +503,14 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void k_scatter_v(const int* __restrict__ rows_R, int n,
                                                         int L_p, int first, int carried_per_seq,
                                                         int d_kv, const T* __restrict__ v_stage,
-                                                        T* __restrict__ v_cache) {
+                                                        T* __restrict__ v_cache,
+                                                        const int* __restrict__ rmap) {
   const int row = rows_R[blockIdx.x];
   const int pos = row % n;
   if (pos < L_p) return;  // uniform over the workgroup
   const size_t i = static_cast<size_t>(row / n) * carried_per_seq + (pos - first);
   const T* src = v_stage + i * d_kv;
-  T* dst = v_cache + static_cast<size_t>(row) * d_kv;
+  T* dst = v_cache + cache_row(rmap, row) * d_kv;
   for (int c = threadIdx.x; c < d_kv; c += kThreads) dst[c] = src[c];
 }
 
@@ -510,6 +522,17 @@ __global__ __launch_bounds__(kThreads) void k_copy_prompt(const T* __restrict__ 
   const T* s = prompt_out + (static_cast<size_t>(b) * L_p + t) * d;
   T* o = hidden_out + (static_cast<size_t>(b) * n + t) * d;
   for (int c = threadIdx.x; c < d; c += kThreads) o[c] = s[c];
+}
+
+// out[row][:] = cache[rmap[row]][:]: a cache tensor in logical row order
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_gather_rows(const T* __restrict__ cache,
+                                                          const int* __restrict__ rmap, int width,
+                                                          T* __restrict__ out) {
+  const int row = blockIdx.x;
+  const T* s = cache + cache_row(rmap, row) * width;
+  T* o = out + static_cast<size_t>(row) * width;
+  for (int c = threadIdx.x; c < width; c += kThreads) o[c] = s[c];
 }
 
 __global__ void k_iota_rows(int* rows, int* inv, int n, int first, int count, int per_seq,
@@ -567,81 +590,81 @@ void launch_embed_norm(const RowKernelArgs& a, const void* hidden_in, const int*
 
 void launch_v_finalize(const RowKernelArgs& a, const float* c_part, int S, int first, int per_seq,
                        int M, int d_kv, void* v_cache, float* score, int metric, void* v_stage,
-                       hipStream_t st) {
+                       hipStream_t st, const int* rmap) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * d_kv;
   const bool vec = vec_ok(d_kv, {c_part, v_cache, v_stage});
   if (a.dtype == 1) {
     DLLMC_ROW_LAUNCH(k_v_finalize, bf16_t, vec, dim3(M), st, c_part, S, stride, first, per_seq, d_kv, a.n, a.L_p,
-                     P<bf16_t>(v_cache), score, metric, P<bf16_t>(v_stage));
+                     P<bf16_t>(v_cache), score, metric, P<bf16_t>(v_stage), rmap);
   } else {
     DLLMC_ROW_LAUNCH(k_v_finalize, float, vec, dim3(M), st, c_part, S, stride, first, per_seq, d_kv, a.n, a.L_p,
-                     P<float>(v_cache), score, metric, P<float>(v_stage));
+                     P<float>(v_cache), score, metric, P<float>(v_stage), rmap);
   }
 }
 
 void launch_scatter_v(const RowKernelArgs& a, const int* rows_R, int M_R, int first,
                       int carried_per_seq, int d_kv, const void* v_stage, void* v_cache,
-                      hipStream_t st) {
+                      hipStream_t st, const int* rmap) {
   if (M_R <= 0) return;
   if (a.dtype == 1)
     hipLaunchKernelGGL(k_scatter_v<bf16_t>, dim3(M_R), dim3(kThreads), 0, st, rows_R, a.n, a.L_p, first,
-                       carried_per_seq, d_kv, P<bf16_t>(v_stage), P<bf16_t>(v_cache));
+                       carried_per_seq, d_kv, P<bf16_t>(v_stage), P<bf16_t>(v_cache), rmap);
   else
     hipLaunchKernelGGL(k_scatter_v<float>, dim3(M_R), dim3(kThreads), 0, st, rows_R, a.n, a.L_p, first,
-                       carried_per_seq, d_kv, P<float>(v_stage), P<float>(v_cache));
+                       carried_per_seq, d_kv, P<float>(v_stage), P<float>(v_cache), rmap);
 }
 
 void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                         int d_q, int d_kv, int d_h, const float2* rope_tab, void* q_out,
-                        void* k_cache, bool rope_second, hipStream_t st) {
+                        void* k_cache, bool rope_second, hipStream_t st, const int* rmap) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * (d_q + d_kv);
   const dim3 grid(M, (d_q + d_kv) / d_h);
   if (a.dtype == 1)
     hipLaunchKernelGGL(k_qk_finalize<bf16_t>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
                        d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache),
-                       rope_second ? 1 : 0);
+                       rope_second ? 1 : 0, rmap);
   else
     hipLaunchKernelGGL(k_qk_finalize<float>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
                        d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache),
-                       rope_second ? 1 : 0);
+                       rope_second ? 1 : 0, rmap);
 }
 
 void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
                        int d_kv, int d_h, const float2* rope_tab, void* k_cache, float* score,
-                       int metric, void* k_stage, hipStream_t st) {
+                       int metric, void* k_stage, hipStream_t st, const int* rmap) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * d_kv;
   if (a.dtype == 1)
     hipLaunchKernelGGL(k_k_finalize<bf16_t>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
                        d_kv, d_h, a.n, a.L_p, rope_tab, P<bf16_t>(k_cache), score, metric,
-                       P<bf16_t>(k_stage));
+                       P<bf16_t>(k_stage), rmap);
   else
     hipLaunchKernelGGL(k_k_finalize<float>, dim3(M), dim3(kThreads), 0, st, c_part, S, stride, rows,
                        d_kv, d_h, a.n, a.L_p, rope_tab, P<float>(k_cache), score, metric,
-                       P<float>(k_stage));
+                       P<float>(k_stage), rmap);
 }
 
 void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows_R,
                        int M_R, void* attn_cache, float* x, const void* gain, void* g_out,
-                       hipStream_t st) {
+                       hipStream_t st, const int* rmap) {
   if (M_R <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
   const bool vec = vec_ok(a.d, {c_part, attn_cache, x, gain, g_out});
   if (a.dtype == 1) {
     DLLMC_ROW_LAUNCH(k_o_finalize, bf16_t, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
-                     P<bf16_t>(attn_cache), x, P<bf16_t>(gain), P<bf16_t>(g_out));
+                     P<bf16_t>(attn_cache), x, P<bf16_t>(gain), P<bf16_t>(g_out), rmap);
   } else {
     DLLMC_ROW_LAUNCH(k_o_finalize, float, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
-                     P<float>(attn_cache), x, P<float>(gain), P<float>(g_out));
+                     P<float>(attn_cache), x, P<float>(gain), P<float>(g_out), rmap);
   }
 }
 
 void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u, hipStream_t st) {
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * 2 * m;
-  const dim3 grid((m + kThreads - 1) / kThreads, M);
+  const dim3 grid(M, (m + kThreads - 1) / kThreads);
   if (dtype == 1)
     hipLaunchKernelGGL(k_swiglu<bf16_t>, grid, dim3(kThreads), 0, st, c_part, S, stride, m,
                        P<bf16_t>(u));
@@ -653,7 +676,7 @@ void launch_swiglu(int dtype, const float* c_part, int S, int M, int m, void* u,
 void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, int M_R,
                           int first, int per_seq, int Mc, const int* inv, const void* attn_cache,
                           void* ffn_cache, float* x, const void* next_gain, void* h,
-                          void* hidden_out, void* prompt_out, hipStream_t st) {
+                          void* hidden_out, void* prompt_out, hipStream_t st, const int* rmap) {
   if (Mc <= 0) return;
   const size_t stride = static_cast<size_t>(M_R) * a.d;
   const bool vec =
@@ -661,11 +684,11 @@ void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, in
   if (a.dtype == 1) {
     DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<bf16_t>(attn_cache), P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
-                     P<bf16_t>(hidden_out), P<bf16_t>(prompt_out));
+                     P<bf16_t>(hidden_out), P<bf16_t>(prompt_out), rmap);
   } else {
     DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<float>(attn_cache), P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
-                     P<float>(hidden_out), P<float>(prompt_out));
+                     P<float>(hidden_out), P<float>(prompt_out), rmap);
   }
 }
 
@@ -679,6 +702,17 @@ void launch_copy_prompt(const RowKernelArgs& a, int B, const void* prompt_out, v
   else
     hipLaunchKernelGGL(k_copy_prompt<float>, grid, dim3(kThreads), 0, st, P<float>(prompt_out), a.n,
                        a.L_p, a.d, P<float>(hidden_out));
+}
+
+void launch_gather_rows(int dtype, const void* cache, const int* rmap, int rows, int width,
+                        void* out, hipStream_t st) {
+  if (rows <= 0) return;
+  if (dtype == 1)
+    hipLaunchKernelGGL(k_gather_rows<bf16_t>, dim3(rows), dim3(kThreads), 0, st, P<bf16_t>(cache), rmap,
+                       width, P<bf16_t>(out));
+  else
+    hipLaunchKernelGGL(k_gather_rows<float>, dim3(rows), dim3(kThreads), 0, st, P<float>(cache), rmap,
+                       width, P<float>(out));
 }
 
 void launch_iota_rows(int* rows, int* inv, int B, int n, int first, int count, int per_seq,

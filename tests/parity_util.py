@@ -83,7 +83,8 @@ def make_pair(cfg: I.Config, weights: List[Dict[str, np.ndarray]], **over):
     gpu = binding.CachedDenoiser(n_layers=cfg.T, d_model=cfg.d, n_q_heads=cfg.H_q,
                                  n_kv_heads=cfg.H_kv, head_dim=cfg.d_h, d_ffn=cfg.m, batch=cfg.B,
                                  dtype=cfg.dtype, weights=dev_ws, L_p=cfg.L_p, L_r=cfg.L_r, rho=rho,
-                                 K_p=K_p, K_r=K_r, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+                                 K_p=K_p, K_r=K_r, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta,
+                                 paging=over.get("paging"))
     policy = {k: over[k] for k in ("metric", "selection", "v_update", "seed", "source") if k in over}
     if policy:
         gpu.set_policy(**policy)

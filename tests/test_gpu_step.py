@@ -404,3 +404,25 @@ def test_update_ratio_per_layer_combined_with_the_variants():
     assert st.worst_rel <= 2e-2
     PU.compare_caches(cfg, gpu, ora, st)
     gpu.close()
+
+
+def test_tuning_is_copied_at_creation_and_live_contexts_keep_theirs():
+    """dllmc_set_gemm_tuning changes the default for contexts created afterwards; a context that
+    already exists keeps the settings it was created with (bit-identical results)."""
+    cfg = MINI_LLADA.replace(steps=4)
+    ws = I.all_weights(cfg)
+    sched = I.TokenSchedule(cfg, stress=True)
+    hid = [PU.to_device(cfg, sched.hidden_in(i)) for i in range(cfg.steps)]
+    ref, _ = PU.make_pair(cfg, ws)
+    want = [ref.step(hid[i], i)[0].clone() for i in range(cfg.steps)]
+    live, _ = PU.make_pair(cfg, ws)
+    got = [live.step(hid[0], 0)[0].clone()]
+    binding.set_gemm_tuning(nw_dual=4, nw=4, force_s=2)
+    try:
+        got += [live.step(hid[i], i)[0].clone() for i in range(1, cfg.steps)]
+    finally:
+        binding.set_gemm_tuning(nw_dual=DEFAULT_NW_DUAL, nw=8, force_s=0)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(got, want))
+    ref.close()
+    live.close()
