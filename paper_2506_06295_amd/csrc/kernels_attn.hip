@@ -201,7 +201,39 @@ __device__ __forceinline__ void attn_finish(const f32x4 (&o_acc)[8], float m_run
   }
 }
 
-// Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; blockIdx.z
+// Workgroups are handed to the 8 XCDs round-robin in launch order and each XCD has its own L2.
+// The launch is one-dimensional: a "slot" is (query tile, KV head, sequence, key range), and the G
+// query heads that share the slot's KV head run back to back on one XCD, so the slot's K and V
+// blocks are fetched into that L2 once instead of once per query head (grouped KV heads: 7 x
+// fewer fetches for 28 / 4 heads).  Slots beyond the last multiple of 8 are walked in order.
+struct AttnWork { int qtile, a, b, ks; };
+__device__ __forceinline__ AttnWork attn_work(int qt, int H_q, int H_kv, int KS) {
+  const int G = H_q / H_kv;
+  const int n_slots = gridDim.x / G;
+  const int lin = blockIdx.x;
+  const int n8 = n_slots & ~7;
+  int slot, j;
+  if (lin < n8 * G) {
+    const int xcd = lin & 7, idx = lin >> 3;
+    slot = (idx / G) * 8 + xcd;
+    j = idx % G;
+  } else {
+    const int rest = lin - n8 * G;
+    slot = n8 + rest / G;
+    j = rest % G;
+  }
+  // slot = ((b * KS + ks) * H_kv + kvh) * qt + qtile
+  AttnWork w;
+  w.qtile = slot % qt;
+  const int kvh = (slot / qt) % H_kv;
+  const int z = slot / (qt * H_kv);
+  w.b = z / KS;
+  w.ks = z % KS;
+  w.a = kvh * G + j;
+  return w;
+}
+
+// Workgroup = 4 wavefronts = 4 tiles of 16 queries of one head and one sequence; the slot
 // enumerates (sequence, key range).  All four wavefronts use the same 32-key blocks, so a V
 // tile is transposed through LDS once per workgroup.  With KS == 1 the normalised output is
 // written; otherwise the un-normalised partial (O, m, l) of this key range goes to `part` for
@@ -215,6 +247,9 @@ __device__ __forceinline__ void attn_finish(const f32x4 (&o_acc)[8], float m_run
 // hit 16 different banks (lanes along the dims with 16-bit stores spend 7 of 8 LDS cycles on
 // bank conflicts), and ch & 14 = 2 * (dim / 16) is the same for all rows of a dim block, so the
 // reader undoes it with a constant.
+// PAGED: the key rows are looked up in the row map (a compile-time switch: the flat layout's
+// code, whose loads must all go out before the first use, stays exactly as it is without it).
+template <bool PAGED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_attn_mfma(
     const bf16_t* __restrict__ q, int Mq, const bf16_t* __restrict__ kc,
     const bf16_t* __restrict__ vc, int n, int H_q, int H_kv, int KS, bf16_t* __restrict__ out,
@@ -222,11 +257,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kPreload][kDH * kVtStride];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int a = blockIdx.y;
-  const int b = blockIdx.z / KS, ks = blockIdx.z % KS;
+  const AttnWork wk = attn_work((Mq + kQT - 1) / kQT, H_q, H_kv, KS);
+  const int a = wk.a, b = wk.b, ks = wk.ks;
   const int d_q = H_q * kDH, d_kv = H_kv * kDH;
   const int kv = a / (H_q / H_kv);
-  const int i0 = blockIdx.x * kQT + wave * 16;  // first query of this wavefront
+  const int i0 = wk.qtile * kQT + wave * 16;  // first query of this wavefront
 
   // key row j of this sequence: cache row b * n + j, or the row map's entry (paged layout)
   const bf16_t* K = kc + kv * kDH;
@@ -265,7 +300,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
       for (int sb = 0; sb < 2; ++sb) {
         int kr = blk * 32 + sb * 16 + ln;
         if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
-        const size_t cr = static_cast<size_t>(rmap ? rmap[seq0 + kr] : seq0 + kr);
+        const size_t cr = static_cast<size_t>(PAGED ? rmap[seq0 + kr] : seq0 + kr);
         const bf16_t* kptr = K + cr * d_kv + lg * 8;
 #pragma unroll
         for (int c = 0; c < 4; ++c) kall[j][sb][c] = *reinterpret_cast<const bf16x8*>(kptr + c * 32);
@@ -274,7 +309,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
       for (int h = 0; h < 2; ++h) {
         int kr = blk * 32 + 2 * kp + h;
         if (kr >= n) kr = n - 1;
-        const size_t cr = static_cast<size_t>(rmap ? rmap[seq0 + kr] : seq0 + kr);
+        const size_t cr = static_cast<size_t>(PAGED ? rmap[seq0 + kr] : seq0 + kr);
         vall[j][h] = *reinterpret_cast<const uint4*>(V + cr * d_kv + ch * 8);
       }
     }
@@ -312,6 +347,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
 constexpr int kWalkStages = 4;
 constexpr int kVtStrideW = 36;  // 32 keys + 4 pad: rows of 8 dims apart start 16 banks apart
 
+template <bool PAGED>
 __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q, int Mq,
                                                    const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, int n, int H_q,
@@ -323,11 +359,11 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kDH * kVtStrideW];
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int a = blockIdx.y;
-  const int b = blockIdx.z / KS, ks = blockIdx.z % KS;
+  const AttnWork wk = attn_work((Mq + kQT - 1) / kQT, H_q, H_kv, KS);
+  const int a = wk.a, b = wk.b, ks = wk.ks;
   const int d_q = H_q * kDH, d_kv = H_kv * kDH;
   const int kv = a / (H_q / H_kv);
-  const int i0 = blockIdx.x * kQT + wave * 16;
+  const int i0 = wk.qtile * kQT + wave * 16;
 
   const bf16_t* K = kc + kv * kDH;
   const bf16_t* V = vc + kv * kDH;
@@ -372,7 +408,7 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
       for (int j = 0; j < 2; ++j) {
         int kr = blk * 32 + lkey[j];
         if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
-        cr[j] = rmap ? rmap[seq0 + kr] : seq0 + kr;
+        cr[j] = PAGED ? rmap[seq0 + kr] : seq0 + kr;
       }
     };
     auto issue = [&](const int (&cr)[2], int stage) {
@@ -406,8 +442,7 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
       const int stage = i % kWalkStages;
       // 4 loads per block and wavefront, kWalkStages - 1 blocks in flight: the oldest has landed
       // (paged layout: the two row-map lookups of the block after those are in flight as well)
-      if (rmap) wait_vmcnt<4 * (kWalkStages - 2) + 2>();
-      else wait_vmcnt<4 * (kWalkStages - 2)>();
+      wait_vmcnt<4 * (kWalkStages - 2) + (PAGED ? 2 : 0)>();
       // everybody's loads of block i have landed, and everybody is done with block i - 1: its
       // stage and Vt may be overwritten
       __builtin_amdgcn_s_barrier();
@@ -502,19 +537,24 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     const int base = B * qt * H_q;  // workgroups without splitting the keys
     const int nblk = (n + 31) / 32;
     int KS = 1;
-    if (scratch != nullptr && base < 512) {
-      KS = (512 + base - 1) / base;
+    // keys are split only while the queries alone leave CUs without a workgroup (384 workgroups of
+    // a 768-row refresh: 54 us split in two with a merge launch, 45 us whole)
+    if (scratch != nullptr && base < 256) {
+      KS = (512 + base - 1) / base;  // aim for ~512 workgroups
       if (KS > kMaxKeySplit) KS = kMaxKeySplit;
       // ranges of three blocks are fetched whole in one trip; shorter ones only add partial
       // results to merge
       if (KS > (nblk + 2) / 3) KS = (nblk + 2) / 3;
     }
-    if ((nblk + KS - 1) / KS <= kPreload)
-      hipLaunchKernelGGL(k_attn_mfma, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
-                         H_kv, KS, oo, scratch, rmap);
-    else
-      hipLaunchKernelGGL(k_attn_walk, dim3(qt, H_q, B * KS), dim3(256), 0, st, qq, Mq, kk, vv, n, H_q,
-                         H_kv, KS, oo, scratch, rmap);
+    const dim3 grid(qt * H_q * B * KS);
+    const bool whole = (nblk + KS - 1) / KS <= kPreload;
+#define DLLMC_ATTN(KERNEL) \
+  hipLaunchKernelGGL(KERNEL, grid, dim3(256), 0, st, qq, Mq, kk, vv, n, H_q, H_kv, KS, oo, scratch, rmap)
+    if (whole && rmap) DLLMC_ATTN(k_attn_mfma<true>);
+    else if (whole) DLLMC_ATTN(k_attn_mfma<false>);
+    else if (rmap) DLLMC_ATTN(k_attn_walk<true>);
+    else DLLMC_ATTN(k_attn_walk<false>);
+#undef DLLMC_ATTN
     if (KS > 8)
       hipLaunchKernelGGL(k_attn_merge<kMaxKeySplit>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS,
                          oo);

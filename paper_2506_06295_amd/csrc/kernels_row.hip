@@ -24,6 +24,12 @@ template <int V> struct Vec { float v[V]; };
 __device__ __forceinline__ size_t cache_row(const int* __restrict__ rmap, int row) {
   return static_cast<size_t>(rmap ? rmap[row] : row);
 }
+// The same with the layout known at compile time: the kernels of the adaptive step's critical
+// path are instantiated twice, so that the flat layout's code carries no trace of the lookup
+// (a run-time test in front of a row's loads cost ~0.3 us per launch).
+template <bool PG> __device__ __forceinline__ size_t cache_row_t(const int* __restrict__ rmap, int row) {
+  return static_cast<size_t>(PG ? rmap[row] : row);
+}
 
 template <int V> __device__ __forceinline__ Vec<V> ld_f32(const float* p);
 template <> __device__ __forceinline__ Vec<1> ld_f32<1>(const float* p) { return {{*p}}; }
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_v_finalize(const float* __restrict
 
 // ---- Q/K epilogue: RoPE at the row's absolute position, Q to the compact buffer, K scatter --
 // grid (rows, query heads + kv heads), one wavefront per (row, head), one lane per pair.
-template <typename T>
+template <typename T, bool PG>
 __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_part, int S,
                                                     size_t slice_stride,
                                                     const int* __restrict__ rows, int n, int d_q,
@@ -285,7 +291,7 @@ __global__ __launch_bounds__(64) void k_qk_finalize(const float* __restrict__ c_
   const float2* tab = rope_tab + static_cast<size_t>(pos) * half;
   const int c0 = head * d_h;  // first column of the head inside [Q | K]
   T* dst = c0 < d_q ? q_out + static_cast<size_t>(i) * d_q + c0
-                    : k_cache + cache_row(rmap, row) * d_kv + (c0 - d_q);
+                    : k_cache + cache_row_t<PG>(rmap, row) * d_kv + (c0 - d_q);
   for (int t = threadIdx.x; t < half; t += 64) {
     const size_t off = static_cast<size_t>(i) * width + c0 + t;
     float2 ab;
@@ -355,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void k_k_finalize(const float* __restrict
 // One workgroup per recomputed row.  Rows that are carried but not recomputed are left alone:
 // their residual add of the cached attention output happens in k_down_finalize, in the same
 // order of additions, so the stream x of such a row is read and written once per layer.
-template <typename T, int V>
+template <typename T, int V, bool PG>
 __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict__ c_part, int S,
                                                          size_t slice_stride,
                                                          const int* __restrict__ rows_R, int d,
@@ -367,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void k_o_finalize(const float* __restrict
   __shared__ float red[kNW];
   const int ci = blockIdx.x;
   const int row = rows_R[ci];
-  T* ac = attn_cache + cache_row(rmap, row) * d;
+  T* ac = attn_cache + cache_row_t<PG>(rmap, row) * d;
   float* xr = x + static_cast<size_t>(row) * d;
   Vec<V> keep[kRegVecs];
   float ss = 0.f;
@@ -419,7 +425,7 @@ __global__ __launch_bounds__(kThreads) void k_swiglu(const float* __restrict__ c
 }
 
 // ---- down projection epilogue + residual + next layer's attention norm / step output ------
-template <typename T, int V>
+template <typename T, int V, bool PG>
 __global__ __launch_bounds__(kThreads) void k_down_finalize(
     const float* __restrict__ c_part, int S, size_t slice_stride, int first, int per_seq,
     const int* __restrict__ inv, int d, int n, int L_p, float eps,
@@ -431,7 +437,7 @@ __global__ __launch_bounds__(kThreads) void k_down_finalize(
   // the row's loads do not wait for a list entry
   const int i = blockIdx.x;
   const int row = (i / per_seq) * n + first + i % per_seq;
-  const size_t crow = cache_row(rmap, row);
+  const size_t crow = cache_row_t<PG>(rmap, row);
   T* fc = ffn_cache + crow * d;
   const T* ac = attn_cache + crow * d;
   float* xr = x + static_cast<size_t>(row) * d;
@@ -569,6 +575,15 @@ inline bool vec_ok(int width, std::initializer_list<const void*> ptrs) {
 }  // namespace
 
 // launch KERNEL<T, 4> or KERNEL<T, 1> depending on whether 16-byte vectors apply
+// the same for kernels with the paged-layout switch as a third template argument
+#define DLLMC_ROW_LAUNCH_PG(KERNEL, T, vec, pg, grid, st, ...)                                       \
+  do {                                                                                               \
+    if (vec && pg) hipLaunchKernelGGL((KERNEL<T, 4, true>), grid, dim3(kThreads), 0, st, __VA_ARGS__);      \
+    else if (vec) hipLaunchKernelGGL((KERNEL<T, 4, false>), grid, dim3(kThreads), 0, st, __VA_ARGS__);      \
+    else if (pg) hipLaunchKernelGGL((KERNEL<T, 1, true>), grid, dim3(kThreads), 0, st, __VA_ARGS__);        \
+    else hipLaunchKernelGGL((KERNEL<T, 1, false>), grid, dim3(kThreads), 0, st, __VA_ARGS__);               \
+  } while (0)
+
 #define DLLMC_ROW_LAUNCH(KERNEL, T, vec, grid, st, ...)                                      \
   do {                                                                                       \
     if (vec) hipLaunchKernelGGL((KERNEL<T, 4>), grid, dim3(kThreads), 0, st, __VA_ARGS__);    \
@@ -621,14 +636,14 @@ void launch_qk_finalize(const RowKernelArgs& a, const float* c_part, int S, cons
   if (M <= 0) return;
   const size_t stride = static_cast<size_t>(M) * (d_q + d_kv);
   const dim3 grid(M, (d_q + d_kv) / d_h);
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_qk_finalize<bf16_t>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
-                       d_q, d_kv, d_h, rope_tab, P<bf16_t>(q_out), P<bf16_t>(k_cache),
-                       rope_second ? 1 : 0, rmap);
-  else
-    hipLaunchKernelGGL(k_qk_finalize<float>, grid, dim3(64), 0, st, c_part, S, stride, rows, a.n,
-                       d_q, d_kv, d_h, rope_tab, P<float>(q_out), P<float>(k_cache),
-                       rope_second ? 1 : 0, rmap);
+#define DLLMC_QK(T, PG)                                                                           \
+  hipLaunchKernelGGL((k_qk_finalize<T, PG>), grid, dim3(64), 0, st, c_part, S, stride, rows, a.n, d_q, \
+                     d_kv, d_h, rope_tab, P<T>(q_out), P<T>(k_cache), rope_second ? 1 : 0, rmap)
+  if (a.dtype == 1 && rmap) DLLMC_QK(bf16_t, true);
+  else if (a.dtype == 1) DLLMC_QK(bf16_t, false);
+  else if (rmap) DLLMC_QK(float, true);
+  else DLLMC_QK(float, false);
+#undef DLLMC_QK
 }
 
 void launch_k_finalize(const RowKernelArgs& a, const float* c_part, int S, const int* rows, int M,
@@ -653,10 +668,10 @@ void launch_o_finalize(const RowKernelArgs& a, const float* c_part, int S, const
   const size_t stride = static_cast<size_t>(M_R) * a.d;
   const bool vec = vec_ok(a.d, {c_part, attn_cache, x, gain, g_out});
   if (a.dtype == 1) {
-    DLLMC_ROW_LAUNCH(k_o_finalize, bf16_t, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
+    DLLMC_ROW_LAUNCH_PG(k_o_finalize, bf16_t, vec, rmap != nullptr, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
                      P<bf16_t>(attn_cache), x, P<bf16_t>(gain), P<bf16_t>(g_out), rmap);
   } else {
-    DLLMC_ROW_LAUNCH(k_o_finalize, float, vec, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
+    DLLMC_ROW_LAUNCH_PG(k_o_finalize, float, vec, rmap != nullptr, dim3(M_R), st, c_part, S, stride, rows_R, a.d, a.eps,
                      P<float>(attn_cache), x, P<float>(gain), P<float>(g_out), rmap);
   }
 }
@@ -682,11 +697,11 @@ void launch_down_finalize(const RowKernelArgs& a, const float* c_part, int S, in
   const bool vec =
       vec_ok(a.d, {c_part, attn_cache, ffn_cache, x, next_gain, h, hidden_out, prompt_out});
   if (a.dtype == 1) {
-    DLLMC_ROW_LAUNCH(k_down_finalize, bf16_t, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
+    DLLMC_ROW_LAUNCH_PG(k_down_finalize, bf16_t, vec, rmap != nullptr, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<bf16_t>(attn_cache), P<bf16_t>(ffn_cache), x, P<bf16_t>(next_gain), P<bf16_t>(h),
                      P<bf16_t>(hidden_out), P<bf16_t>(prompt_out), rmap);
   } else {
-    DLLMC_ROW_LAUNCH(k_down_finalize, float, vec, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
+    DLLMC_ROW_LAUNCH_PG(k_down_finalize, float, vec, rmap != nullptr, dim3(Mc), st, c_part, S, stride, first, per_seq, inv, a.d,
                      a.n, a.L_p, a.eps, P<float>(attn_cache), P<float>(ffn_cache), x, P<float>(next_gain), P<float>(h),
                      P<float>(hidden_out), P<float>(prompt_out), rmap);
   }
