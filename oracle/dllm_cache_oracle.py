@@ -22,7 +22,9 @@ What it follows
   named by the workloads; the paper only names "bidirectional attention" and
   the three SwiGLU matmuls.
 
-Arithmetic is float64 by default.  `storage="bf16"` rounds every tensor that a
+Arithmetic is float64 by default.  `storage="bf16_cache"` rounds only what is
+written into a cache and the step's output (the narrowest reading of the
+paper's bf16 caches).  `storage="bf16"` rounds every tensor that a
 bf16 implementation materialises (normed rows, Q, K, V, attention rows,
 AttnOut, FFN-normed rows, the SwiGLU product, FFNOut, the step's output) to the
 bf16 grid once, at the point it is produced; the residual stream inside a step
@@ -233,7 +235,7 @@ def uncached_forward(model: Model, weights: Sequence[Dict[str, np.ndarray]],
 
     hidden_in: [B, n, d].  Returns the residual stream after the last block.
     """
-    st = _store_fn(storage)
+    st, stc = _store_fn(storage), _cache_store_fn(storage)
     B, n, d = hidden_in.shape
     out = np.empty((B, n, d), dtype=dtype)
     pos = np.arange(n)
@@ -243,23 +245,36 @@ def uncached_forward(model: Model, weights: Sequence[Dict[str, np.ndarray]],
             W = _as(weights[l], dtype)
             h = st(rmsnorm(x, W["attn_norm_g"], model.rms_eps))
             q = st(rope(h @ W["wq"].T, pos, model.d_h, model.rope_theta))
-            k = st(rope(h @ W["wk"].T, pos, model.d_h, model.rope_theta))
-            v = st(h @ W["wv"].T)
+            k = stc(rope(h @ W["wk"].T, pos, model.d_h, model.rope_theta))
+            v = stc(h @ W["wv"].T)
             a = st(attention(q, k, v, model.H_q, model.H_kv, model.d_h))
-            x = x + st(a @ W["wo"].T)
+            x = x + stc(a @ W["wo"].T)
             g = st(rmsnorm(x, W["ffn_norm_g"], model.rms_eps))
             u = st(silu(g @ W["w_gate"].T) * (g @ W["w_up"].T))
-            x = x + st(u @ W["w_down"].T)
-        out[b] = st(x)
+            x = x + stc(u @ W["w_down"].T)
+        out[b] = stc(x)
     return out
 
 
 def _store_fn(storage: str):
-    if storage == "f64":
+    """Rounding applied where a bf16 implementation materialises an intermediate tensor."""
+    if storage in ("f64", "bf16_cache"):
         return lambda a: a
     if storage == "bf16":
         return round_bf16
-    raise ValueError("storage must be 'f64' or 'bf16'")
+    raise ValueError("storage must be 'f64', 'bf16' or 'bf16_cache'")
+
+
+def _cache_store_fn(storage: str):
+    """Rounding applied to what is written into a cache (K, V, AttnOut, FFNOut) and to the
+    step's output.  'bf16_cache' is the narrowest reading of the paper's statement that the
+    caches are held in bfloat16 (storage-overhead proof): only those tensors are rounded, every
+    intermediate stays in the working precision."""
+    if storage == "f64":
+        return lambda a: a
+    if storage in ("bf16", "bf16_cache"):
+        return round_bf16
+    raise ValueError("storage must be 'f64', 'bf16' or 'bf16_cache'")
 
 
 def _as(W: Dict[str, np.ndarray], dtype) -> Dict[str, np.ndarray]:
@@ -323,6 +338,7 @@ class CachedDenoiser:
             self.k_layers = [num_selected(r, L_r) for r in rho_layers]
         self.storage, self.dtype = storage, dtype
         self._st = _store_fn(storage)
+        self._stc = _cache_store_fn(storage)
         T, n = model.T, self.n
         z = lambda w: [np.zeros((B, n, w), dtype=dtype) for _ in range(T)]
         self.K, self.V = z(model.d_kv), z(model.d_kv)
@@ -348,7 +364,7 @@ class CachedDenoiser:
         selection is applied and may return a replacement index array.
         Returns (hidden_out [B, n, d], StepReport).
         """
-        mo, st, dt = self.model, self._st, self.dtype
+        mo, st, stc, dt = self.model, self._st, self._stc, self.dtype
         L_p, L_r, n = self.L_p, self.L_r, self.n
         P, Rf = self.step_kind(i)
         if i == 0:
@@ -371,10 +387,10 @@ class CachedDenoiser:
                 # the verified tensor (V by default, K after RoPE for K-verify) of every carried row
                 k_src = self.source == "k"
                 if k_src:
-                    T_new = st(rope(h @ W["wk"].T, C, mo.d_h, mo.rope_theta))
+                    T_new = stc(rope(h @ W["wk"].T, C, mo.d_h, mo.rope_theta))
                     cache = self.K[l]
                 else:
-                    T_new = st(h @ W["wv"].T)
+                    T_new = stc(h @ W["wv"].T)
                     cache = self.V[l]
                 self.macs += h.shape[0] * mo.d * mo.d_kv
                 if Rf:
@@ -409,24 +425,24 @@ class CachedDenoiser:
                     hR = h[R - off]
                     Q_R = st(rope(hR @ W["wq"].T, R, mo.d_h, mo.rope_theta))
                     if k_src:
-                        self.V[l][b, R] = st(hR @ W["wv"].T)
+                        self.V[l][b, R] = stc(hR @ W["wv"].T)
                     else:
-                        self.K[l][b, R] = st(rope(hR @ W["wk"].T, R, mo.d_h, mo.rope_theta))
+                        self.K[l][b, R] = stc(rope(hR @ W["wk"].T, R, mo.d_h, mo.rope_theta))
                     self.macs += R.size * mo.d * (mo.d_q + mo.d_kv)
                     # queries in R attend to all n cached keys/values (updated above)
                     A_R = st(attention(Q_R, self.K[l][b], self.V[l][b], mo.H_q, mo.H_kv, mo.d_h))
                     self.macs += 2 * R.size * n * mo.d_q
-                    self.AttnOut[l][b, R] = st(A_R @ W["wo"].T)
+                    self.AttnOut[l][b, R] = stc(A_R @ W["wo"].T)
                     self.macs += R.size * mo.d_q * mo.d
                 # residual: fresh rows and cached rows alike come from the cache
                 x = x + self.AttnOut[l][b, C]
                 if R.size:
                     g = st(rmsnorm(x[R - off], W["ffn_norm_g"], mo.rms_eps))
                     u = st(silu(g @ W["w_gate"].T) * (g @ W["w_up"].T))
-                    self.FFNOut[l][b, R] = st(u @ W["w_down"].T)
+                    self.FFNOut[l][b, R] = stc(u @ W["w_down"].T)
                     self.macs += 3 * R.size * mo.d * mo.m
                 x = x + self.FFNOut[l][b, C]
-            x = st(x)
+            x = stc(x)
             if P:
                 self.prompt_hidden_out[b] = x[:L_p]
             hidden_out[b, :L_p] = self.prompt_hidden_out[b]

@@ -351,3 +351,38 @@ def test_llada_shape_cost_and_storage_figures(golden_dir):
     den = O.CachedDenoiser(O.Model(2, 64, 4, 4, 16, 96), [None, None], 3, 5, 7, 0.25, 4, 2)
     held = sum(a.size for nm in ("K", "V", "AttnOut", "FFNOut") for a in getattr(den, nm))
     assert held == 3 * O.cache_elements(2, 12, 64)
+
+
+def test_cache_only_rounding_mode_rounds_caches_and_output_and_nothing_else():
+    """storage="bf16_cache": the narrowest reading of the paper's bf16 caches (storage-overhead
+    proof): K, V, AttnOut, FFNOut and the step output are on the bf16 grid, intermediates are
+    not rounded (so the result differs from the all-tensors reading, but only by rounding noise),
+    and rho = 1, K_p = K_r = 1 still equals the uncached forward of the same mode."""
+    import numpy as np
+    from oracle import dllm_cache_oracle as O
+    from paper_2506_06295_amd import inputs as I
+    cfg = I.Config("pin", T=2, d=64, H_q=4, H_kv=2, d_h=16, m=96, B=1, L_p=6, L_r=10, steps=4,
+                   rho=0.3, K_p=3, K_r=2, dtype="bf16", vocab=64)
+    ws = [{k: v.astype(np.float64) for k, v in w.items()} for w in I.all_weights(cfg)]
+    model = O.Model(cfg.T, cfg.d, cfg.H_q, cfg.H_kv, cfg.d_h, cfg.m)
+    sched = I.TokenSchedule(cfg, stress=True)
+    outs = {}
+    for mode in ("bf16_cache", "bf16", "f64"):
+        den = O.CachedDenoiser(model, ws, 1, cfg.L_p, cfg.L_r, cfg.rho, cfg.K_p, cfg.K_r, storage=mode)
+        for i in range(4):
+            out, _ = den.step(sched.hidden_in(i).astype(np.float64), i)
+        outs[mode] = (out, den)
+    out, den = outs["bf16_cache"]
+    on_grid = lambda a: np.array_equal(a, O.round_bf16(a))
+    assert on_grid(out) and all(on_grid(getattr(den, t)[l]) for t in ("K", "V", "AttnOut", "FFNOut") for l in range(cfg.T))
+    rel = lambda a, b: np.linalg.norm(a - b) / np.linalg.norm(b)
+    assert 0 < rel(out, outs["bf16"][0]) < 2e-2 and 0 < rel(out, outs["f64"][0]) < 2e-2
+    # fewer rounding points: closer to the unrounded evaluation than the all-tensors reading is
+    assert rel(out, outs["f64"][0]) <= rel(outs["bf16"][0], outs["f64"][0]) * 1.5
+    unc = O.CachedDenoiser(model, ws, 1, cfg.L_p, cfg.L_r, 1.0, 1, 1, storage="bf16_cache")
+    for i in range(2):
+        h = sched.hidden_in(i).astype(np.float64)
+        got, _ = unc.step(h, i)
+        assert np.array_equal(got, O.uncached_forward(model, ws, h, storage="bf16_cache"))
+    with pytest.raises(ValueError):
+        O.CachedDenoiser(model, ws, 1, cfg.L_p, cfg.L_r, 0.3, 3, 2, storage="fp8")
