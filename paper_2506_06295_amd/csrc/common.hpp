@@ -22,6 +22,25 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return static_cast<bf16_t>(u >> 16);
 }
 
+// two floats -> two bf16 (round to nearest even; the hardware's packed conversion), `lo` in the
+// low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+// value of lane (l ^ 1) / (l ^ 2) of the same quad, and of lane 7 - (l % 8) of the same group of
+// eight (data-parallel-primitive moves: no LDS traffic)
+__device__ __forceinline__ float dpp_xor1(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float dpp_xor2(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float dpp_half_mirror(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false));
+}
+
 template <typename T> __device__ __forceinline__ float ldf(const T* p);
 template <> __device__ __forceinline__ float ldf<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float ldf<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -91,6 +110,15 @@ __device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
 // s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// ... and lgkmcnt(0): at most N vector-memory operations outstanding AND every LDS operation of
+// this wavefront complete.  Needed in front of a barrier that hands an LDS stage back to
+// global_load_lds: a fragment read that has been issued but not executed when the wavefront
+// passes the barrier can be overtaken by the data of the next load into that stage (which does
+// not queue behind LDS instructions), and the compiler is free to place the wait for such a read
+// behind the barrier.
+template <int N> __device__ __forceinline__ void wait_vmcnt_lds() {
+  __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
 }
 
 // ---- host-side launchers (defined in the kernels_*.hip files) --------------------------
@@ -258,6 +286,18 @@ int vverify_col_tiles(int N);
 void launch_vverify_fused(const void* A, int lda, int M, int first, int per_seq, int n, int L_p,
                           const void* W, int N, int K, void* v_cache, float* part, int part_stride,
                           int metric, hipStream_t st, const int* rmap = nullptr);
+// The same V-verify, and the Q | K projection with RoPE and the cache scatter, finished in the
+// epilogue of the 128 x 128 / 256 x 256 tile kernels (one slice, no float32 partial sums, no row
+// kernel) for launches with enough rows to fill the chip that way.  Arguments as for
+// launch_vverify_fused / launch_gemm + launch_qk_finalize.  Return false (nothing launched) when
+// the shape is not handled.
+bool launch_gemm_vverify_tiles(int dtype, const void* A, int lda, int M, int first, int per_seq, int n,
+                               int L_p, const void* W, int N, int K, void* v_cache, float* part,
+                               int part_stride, int metric, const int* rmap, hipStream_t st);
+bool launch_gemm_qk_tiles(int dtype, const void* A, int lda, const int* rows, int M, const void* wq,
+                          const void* w2, int d_q, int d_kv, int d_h, int K, const float2* rope_tab,
+                          int n, void* q_out, void* cache, bool rope_second, const int* rmap,
+                          hipStream_t st);
 // score[i] = cosine (metric 0) or minus distance (metric 1) from the tile sums, i < count
 void launch_scores_from_part(const float* part, int n_ct, int count, int metric, float* score,
                              hipStream_t st);

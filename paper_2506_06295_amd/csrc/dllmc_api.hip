@@ -456,22 +456,36 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     // (free until this layer's attention) for the selection
     const bool defer_v = c->v_selected_only && !Rf;
     // The default method in one launch: projection, rounding, the sums of Eq. (cos_sim) per row
-    // and column tile, cache overwrite; the selection kernel forms the scores.
-    const bool fused_v = !ksrc && !defer_v && vverify_fused_ok(dt, h, d, Mc, w.wv, d_kv, d, Vc);
-    const bool part_scores = fused_v && !Rf && !c->random_sel;
-    if (fused_v) {
-      Timed t(c, DLLMC_KC_GEMM_V, (static_cast<double>(d_kv) * d + static_cast<double>(Mc) * d) * esz +
-                                      (Rf ? 1.0 : 2.0) * Mc * d_kv * esz,
-              gemm_flops(Mc, d_kv, d));
-      gemm_clear_last_stream();
-      launch_vverify_fused(h, d, Mc, P ? 0 : L_p, carried_per_seq, n, L_p, w.wv, d_kv, d, Vc,
-                           part_scores ? part : nullptr, B * L_r, c->metric, st, rmap);
-    } else {
+    // and column tile, cache overwrite (the selection kernel forms the scores): 64 x 64 tiles over
+    // the whole contraction range for up to two tiles per CU, the epilogue of the 128 x 128 /
+    // 256 x 256 tile kernels for launches that fill the chip in one slice; else the split
+    // contraction and a row kernel.
+    const bool want_scores = !Rf && !c->random_sel;
+    bool fused_v = false;
+    {
       Timed t(c, DLLMC_KC_GEMM_V, gemm_bytes(Mc, d_kv, d), gemm_flops(Mc, d_kv, d));
-      S = launch_gemm(dt, h, d, carried, Mc, ksrc ? w.wk : w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap,
-                      st);
-      if (S == 0) return DLLMC_ENOMEM;
+      if (!ksrc && !defer_v) {
+        if (vverify_fused_ok(dt, h, d, Mc, w.wv, d_kv, d, Vc)) {
+          gemm_clear_last_stream();
+          launch_vverify_fused(h, d, Mc, P ? 0 : L_p, carried_per_seq, n, L_p, w.wv, d_kv, d, Vc,
+                               want_scores ? part : nullptr, B * L_r, c->metric, st, rmap);
+          fused_v = true;
+        } else {
+          fused_v = launch_gemm_vverify_tiles(dt, h, d, Mc, P ? 0 : L_p, carried_per_seq, n, L_p, w.wv,
+                                              d_kv, d, Vc, want_scores ? part : nullptr, B * L_r,
+                                              c->metric, rmap, st);
+        }
+      }
+      if (fused_v) {
+        t.bytes = (static_cast<double>(d_kv) * d + static_cast<double>(Mc) * d) * esz +
+                  (Rf ? 1.0 : 2.0) * Mc * d_kv * esz;
+      } else {
+        S = launch_gemm(dt, h, d, carried, Mc, ksrc ? w.wk : w.wv, nullptr, d_kv, d_kv, d, cws, cws_cap,
+                        st);
+        if (S == 0) return DLLMC_ENOMEM;
+      }
     }
+    const bool part_scores = fused_v && want_scores;
     if (!fused_v) {
       Timed t(c, DLLMC_KC_ROW, Mc * d_kv * (4.0 + 2.0 * esz), 0);
       float* sc_out = (Rf || c->random_sel) ? nullptr : sc;
@@ -494,14 +508,21 @@ int dllmc_step(dllmc_ctx* c, const void* hidden_in, int32_t step_idx, void* hidd
     }
     S = 1;
     if (M_R > 0) {
+      bool qk_direct;
       {
-        // Q and the other projection (K; V for K-verify) of the recomputed rows in one launch
+        // Q and the other projection (K; V for K-verify) of the recomputed rows in one launch;
+        // with enough rows to fill the chip in one slice, RoPE, the compact Q buffer and the cache
+        // scatter happen in the tile kernel's epilogue
         Timed t(c, DLLMC_KC_GEMM_QK, gemm_bytes(M_R, d_q + d_kv, d), gemm_flops(M_R, d_q + d_kv, d));
-        S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, ksrc ? w.wv : w.wk, d_q, d_q + d_kv, d, cws,
-                        cws_cap, st);
-        if (S == 0) return DLLMC_ENOMEM;
+        qk_direct = launch_gemm_qk_tiles(dt, h, d, rows_R, M_R, w.wq, ksrc ? w.wv : w.wk, d_q, d_kv, d_h,
+                                         d, rope_tab, n, qbuf, ksrc ? Vc : Kc, !ksrc, rmap, st);
+        if (!qk_direct) {
+          S = launch_gemm(dt, h, d, rows_R, M_R, w.wq, ksrc ? w.wv : w.wk, d_q, d_q + d_kv, d, cws,
+                          cws_cap, st);
+          if (S == 0) return DLLMC_ENOMEM;
+        }
       }
-      {
+      if (!qk_direct) {
         Timed t(c, DLLMC_KC_ROW, M_R * (d_q + d_kv) * (4.0 + esz), 0);
         launch_qk_finalize(ra, cws, S, rows_R, M_R, d_q, d_kv, d_h, rope_tab, qbuf, ksrc ? Vc : Kc,
                            !ksrc, st, rmap);

@@ -347,16 +347,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
 constexpr int kWalkStages = 4;
 constexpr int kVtStrideW = 36;  // 32 keys + 4 pad: rows of 8 dims apart start 16 banks apart
 
+// (The body is a function of its own with restrict-qualified parameters, inlined into the kernel:
+// only then does the compiler keep the global -> LDS loads of the later stages in flight across
+// the LDS reads of the landed one; written directly into the kernel it waits for every load in
+// flight before each of those reads, and the walk is bound by one memory latency per block.  The
+// waits that order the loads against the reads are the explicit ones below.)
 template <bool PAGED>
-__global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q, int Mq,
-                                                   const bf16_t* __restrict__ kc,
-                                                   const bf16_t* __restrict__ vc, int n, int H_q,
-                                                   int H_kv, int KS, bf16_t* __restrict__ out,
-                                                   float* __restrict__ part,
-                                                   const int* __restrict__ rmap) {
-  // [stage][K tile, V tile][32 keys][16 slots of 16 bytes]
-  __shared__ __attribute__((aligned(1024))) uint4 tiles[kWalkStages][2][32 * 16];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[kDH * kVtStrideW];
+__device__ __forceinline__ void attn_walk_body(const bf16_t* __restrict__ q, int Mq,
+                                               const bf16_t* __restrict__ kc,
+                                               const bf16_t* __restrict__ vc, int n, int H_q,
+                                               int H_kv, int KS, bf16_t* __restrict__ out,
+                                               float* __restrict__ part,
+                                               const int* __restrict__ rmap) {
+  // [stage][K tile, V tile][32 keys][16 slots of 16 bytes], then the transposed V tile.  One LDS
+  // object on purpose: with two, the compiler cannot tell reads of the landed stage from the
+  // loads in flight into the other stages and waits for all of those before every read.
+  constexpr int kTileVecs = kWalkStages * 2 * 32 * 16;
+  __shared__ __attribute__((aligned(1024))) uint4 smem[kTileVecs + kDH * kVtStrideW * 2 / 16];
+  uint4 (*tiles)[2][32 * 16] = reinterpret_cast<uint4 (*)[2][32 * 16]>(smem);
+  bf16_t* Vt = reinterpret_cast<bf16_t*>(smem + kTileVecs);
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const AttnWork wk = attn_work((Mq + kQT - 1) / kQT, H_q, H_kv, KS);
@@ -476,6 +485,16 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
     __builtin_amdgcn_s_waitcnt(0x0F70);  // the repeated loads past the range, before the LDS goes away
   }
   attn_finish(o_acc, m_run, l_run, i0 + ln, Mq, b, a, ks, KS, H_q, lg, out, part);
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q, int Mq,
+                                                   const bf16_t* __restrict__ kc,
+                                                   const bf16_t* __restrict__ vc, int n, int H_q,
+                                                   int H_kv, int KS, bf16_t* __restrict__ out,
+                                                   float* __restrict__ part,
+                                                   const int* __restrict__ rmap) {
+  attn_walk_body<PAGED>(q, Mq, kc, vc, n, H_q, H_kv, KS, out, part, rmap);
 }
 
 // out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.

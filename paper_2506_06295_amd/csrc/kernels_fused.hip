@@ -128,9 +128,10 @@ __global__ __launch_bounds__(256 * KH) void k_vverify_tile(
     // this wavefront's loads of step kt have landed: the younger steps in flight are
     // min(steps left, kVStages - 2), four loads each
     const int rem = nkt - 1 - kt;
-    if (rem >= 2) wait_vmcnt<8>();
-    else if (rem == 1) wait_vmcnt<4>();
-    else wait_vmcnt<0>();
+    // (with every LDS read of this wavefront complete: see wait_vmcnt_lds)
+    if (rem >= 2) wait_vmcnt_lds<8>();
+    else if (rem == 1) wait_vmcnt_lds<4>();
+    else wait_vmcnt_lds<0>();
     // everybody's loads of step kt have landed, and everybody has finished reading step kt - 1,
     // whose stage the loads of step kt + 3 overwrite
     __builtin_amdgcn_s_barrier();

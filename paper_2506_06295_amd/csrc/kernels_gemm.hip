@@ -342,19 +342,49 @@ constexpr int kMidM = 128, kMidN = 128;
 //        (gate) followed by the same BN/2 rows of W1 (up), so every lane ends up with the gate
 //        and the up sum of the same output element and stores bf16(silu(gate) * up) to U[M, N]
 //        (N = FFN width; the grid has N / (BN/2) column tiles).
-template <int WM, int WN, int MI, int NJ, int PAIR = 0>
+//   EPI = 1 / 2 (single slice): the step's work on the tile is finished in the epilogue, nothing
+//        goes through float32 slices and no row kernel follows.
+//        1: V-verify (Sec. 3.2.2, Eq. cos_sim).  Activation row i is carried row i of the step
+//           (position first + i % per_seq of sequence i / per_seq); the sums are rounded to bf16,
+//           scored against the cached row they replace (per row and 64-column block the three
+//           sums go to `part`, laid out as for k_vverify_tile) and written to the cache.
+//        2: Q | K with RoPE.  A tile column block of 128 is one head, two column wavefronts; the
+//           weight rows are dealt so that a lane's accumulators j and j + 2 hold the rotation pair
+//           (t, t + 64): rotated in registers, query heads go to the compact q_out[i] and the
+//           other heads to cache row rows[i].
+struct TileEpilogue {
+  // EPI = 1
+  int first, per_seq, n, L_p;
+  bf16_t* cache;         // V cache [*, N] (EPI 1); K (or V) cache [*, d_kv] (EPI 2)
+  float* part;           // tile sums, or nullptr: no scoring
+  int part_stride, metric;
+  const int* rmap;       // paged layout: cache row of a logical row, or nullptr
+  // EPI = 2
+  const float2* tab;     // [n][64] (cos, sin)
+  bf16_t* q_out;         // [M, N0]
+  int d_kv, rope_second;
+};
+
+template <int WM, int WN, int MI, int NJ, int PAIR = 0, int EPI = 0>
 __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int lda,
                                               const int* __restrict__ rows, int M,
                                               const bf16_t* __restrict__ W0,
                                               const bf16_t* __restrict__ W1, int N0, int N, int K,
                                               int k_per_slice, float* __restrict__ C,
-                                              bf16_t* __restrict__ U = nullptr) {
+                                              bf16_t* __restrict__ U = nullptr,
+                                              const TileEpilogue* ep = nullptr) {
   constexpr int NWV = WM * WN;
   constexpr int BM = WM * MI * 16, BN = WN * NJ * 16;
   constexpr int LA = BM / 8 / NWV, LB = BN / 8 / NWV;  // load instructions per wavefront and step
   static_assert(BM % (8 * NWV) == 0 && BN % (8 * NWV) == 0, "loader must divide evenly");
   // [stage][activation rows, then weight rows][8 slots], 16 bytes each
-  __shared__ __attribute__((aligned(1024))) uint4 lds[2][(BM + BN) * 8];
+  // (EPI: followed by two ints per tile row, see below.  One LDS object on purpose: with a second
+  // one the compiler can no longer tell the fragment reads from the loads in flight into the
+  // other stage and waits for those before every read.)
+  constexpr int kStage = (BM + BN) * 8;
+  __shared__ __attribute__((aligned(1024))) uint4 lds_all[2 * kStage + (EPI ? 2 * BM / 4 : 0)];
+  uint4 (*lds)[kStage] = reinterpret_cast<uint4 (*)[kStage]>(lds_all);
+  int (*meta)[BM] = reinterpret_cast<int (*)[BM]>(lds_all + 2 * kStage);
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int wm = wave / WN, wn = wave % WN;
@@ -376,7 +406,9 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
     const int chunk = (lane % 8) ^ (r % 8);
     int m = m0 + r;
     if (m >= M) m = M - 1;
-    const int row = rows ? rows[m] : m;
+    int row;
+    if (EPI == 1) row = (m / ep->per_seq) * ep->n + ep->first + m % ep->per_seq;
+    else row = rows ? rows[m] : m;
     asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + chunk * 8;
   }
 #pragma unroll
@@ -388,9 +420,30 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
       const int nn = n0 + (r % (BN / 2));  // < N: N % (BN/2) == 0
       bsrc[j] = (r < BN / 2 ? W0 : W1) + static_cast<size_t>(nn) * K + kbeg + chunk * 8;
     } else {
-      const int nn = n0 + r;  // < N: N % BN == 0
+      // EPI 2: LDS weight row wn*64 + j*16 + c is column (j/2)*64 + (wn%2)*32 + (j%2)*16 + c of head
+      // wn/2 of the tile, so that a lane's accumulators j and j + 2 are a rotation pair
+      const int rp = EPI == 2 ? (r / 128) * 128 + ((r % 64) / 32) * 64 + ((r / 64) % 2) * 32 + r % 32 : r;
+      const int nn = n0 + rp;  // < N: N % BN == 0
       bsrc[j] = (nn < N0 ? W0 + static_cast<size_t>(nn) * K
                          : W1 + static_cast<size_t>(nn - N0) * K) + kbeg + chunk * 8;
+    }
+  }
+  // EPI: what the epilogue needs to know about the tile's rows, looked up here so that the trips
+  // to memory pass under the main loop.  EPI 1: cache row, index of the row's score (-1: not
+  // scored); EPI 2: position in the sequence, cache row.
+  if (EPI != 0 && threadIdx.x < BM) {
+    const int r = threadIdx.x;
+    const int m = min(m0 + r, M - 1);
+    if (EPI == 1) {
+      const int seq = m / ep->per_seq, pos = ep->first + m % ep->per_seq;
+      const int row = seq * ep->n + pos;
+      meta[0][r] = ep->rmap ? ep->rmap[row] : row;
+      meta[1][r] = (m0 + r < M && ep->part != nullptr && pos >= ep->L_p)
+                                 ? seq * (ep->n - ep->L_p) + (pos - ep->L_p) : -1;
+    } else {
+      const int row = rows ? rows[m] : m;
+      meta[0][r] = row % ep->n;
+      meta[1][r] = ep->rmap ? ep->rmap[row] : row;
     }
   }
 #define DLLMC_LDS_ISSUE(stage, kt)                                                              \
@@ -419,7 +472,9 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
     const int cur = kt & 1;
     const bool more = kt + 1 < nkt;
     if (ONE_BARRIER) {
-      wait_vmcnt<0>();  // this wavefront's loads of step kt have landed
+      // this wavefront's loads of step kt have landed and its fragment reads of step kt-1 are
+      // complete (not merely issued: the loads below overwrite their stage)
+      wait_vmcnt_lds<0>();
       __builtin_amdgcn_s_barrier();
       if (more) DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
     } else {
@@ -456,12 +511,160 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
-    // two-barrier scheme: all LDS reads of this stage are complete (their results fed the MFMAs
-    // above) before the loads issued at the top of the next iteration overwrite it
-    if (!ONE_BARRIER) __builtin_amdgcn_s_barrier();
+    // two-barrier scheme: all fragment reads of this stage are complete before the loads issued
+    // at the top of the next iteration overwrite it.  The explicit wait matters: without it the
+    // compiler puts the wait for the last reads (and the MFMAs they feed) behind the barrier, and
+    // a load that hits in L1 (the neighbouring workgroup on the CU reads the same activation rows)
+    // can land before those reads execute.
+    if (!ONE_BARRIER) {
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
+    }
   }
 #undef DLLMC_LDS_ISSUE
 
+  if (EPI != 0) {
+    // Epilogues that finish the step's work on the tile.  A wavefront's 16-row x 64-column block of
+    // results (rounded to bf16) is staged through a private piece of LDS so that it leaves, and
+    // the cached rows it is compared with arrive, as 16-byte pieces of contiguous row segments:
+    // lane l then holds columns 8*(l%8) .. +8 of block rows l/8 and l/8 + 8.
+    static_assert(EPI == 0 || NJ == 4, "a wavefront's block is 64 columns wide");
+    static_assert(EPI != 2 || WN % 2 == 0, "a head is two column wavefronts");
+    constexpr int kStg = 72;  // staging row stride in elements: 64 columns + 16 bytes
+    static_assert(NWV * 16 * kStg * sizeof(bf16_t) <= kStage * sizeof(uint4), "staging fits a stage");
+    __syncthreads();  // everybody has finished the fragment reads of the last step
+    uint32_t* stg32 = reinterpret_cast<uint32_t*>(&lds[0][0]) + wave * (16 * kStg / 2);
+    const bf16_t* stg = reinterpret_cast<const bf16_t*>(stg32);
+    const int rr = lane / 8, ch = lane % 8;
+    const int odd = ln & 1;
+    // EPI 2: the wavefront's columns are pairs (t, t + 64) of one head, t = tb .. tb + 31 (see the
+    // weight loader), staged as two runs of 32
+    const int tb = (wn % 2) * 32;
+    const int head0 = n0 + (wn / 2) * 128;  // first column of the head in [W0; W1]
+    const bool is_q = head0 < N0;
+    const bool rot = is_q || ep->rope_second != 0;
+    const int run = (ch / 4) * 64 + tb + (ch % 4) * 8;  // column inside the head of this lane's piece
+    const int n_ct = N / 64, ct = col_tile * WN + wn;
+    // rotation factors of block i for this lane's rows lg*4 + e and pairs tb + j*16 + ln, or the old
+    // rows of block i (EPI 1): requested one block ahead
+    float2 cs[2][4];
+    uint4 old[2];
+    auto request = [&](int i) {
+      const int rb = wm * (MI * 16) + i * 16;  // first row of the block inside the tile
+      if (EPI == 2) {
+        if (rot) {
+          const int4 pos = *reinterpret_cast<const int4*>(&meta[0][rb + lg * 4]);
+          const int p4[4] = {pos.x, pos.y, pos.z, pos.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              cs[j][e] = ep->tab[static_cast<size_t>(p4[e]) * 64 + tb + j * 16 + ln];
+        }
+      } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          old[h] = make_uint4(0u, 0u, 0u, 0u);
+          const int r = rb + rr + 8 * h;
+          if (meta[1][r] >= 0)
+            old[h] = *reinterpret_cast<const uint4*>(ep->cache + static_cast<size_t>(meta[0][r]) * N + n0 +
+                                                     wn * 64 + ch * 8);
+        }
+      }
+    };
+    if (!rot) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) cs[0][e] = cs[1][e] = make_float2(1.f, 0.f);
+    }
+    request(0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int rb = wm * (MI * 16) + i * 16;
+      // final values of the lane's accumulator elements
+      float val[NJ][4];
+      uint4 old_i[2] = {old[0], old[1]};
+      if (EPI == 2) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const float x0 = acc[i][j][e], x1 = acc[i][j + 2][e];
+            val[j][e] = x0 * cs[j][e].x - x1 * cs[j][e].y;
+            val[j + 2][e] = x1 * cs[j][e].x + x0 * cs[j][e].y;
+          }
+      } else {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) val[j][e] = acc[i][j][e];
+      }
+      if (i + 1 < MI) request(i + 1);
+      // Neighbouring lanes hold neighbouring columns of the same four rows: they trade one value
+      // of each row pair, after which the even lane owns columns (ln, ln + 1) of row e and the odd
+      // lane columns (ln - 1, ln) of row e + 1, one 32-bit store each.
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+          const float got = dpp_xor1(odd ? val[j][e] : val[j][e + 1]);
+          const float lo = odd ? got : val[j][e];
+          const float hi = odd ? val[j][e + 1] : got;
+          const int r = lg * 4 + e + odd;
+          stg32[(r * kStg + j * 16 + (ln & ~1)) / 2] = pack_bf16x2(lo, hi);
+        }
+      // the wavefront's own stores have completed before its loads are issued
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = rb + rr + 8 * h;  // row inside the tile
+        const uint4 nv = *reinterpret_cast<const uint4*>(stg + (rr + 8 * h) * kStg + ch * 8);
+        const int crow = meta[EPI == 1 ? 0 : 1][r];
+        if (EPI == 1) {
+          const int sidx = meta[1][r];
+          if (ep->part != nullptr) {  // uniform
+            const uint32_t nw4[4] = {nv.x, nv.y, nv.z, nv.w};
+            const uint32_t ow4[4] = {old_i[h].x, old_i[h].y, old_i[h].z, old_i[h].w};
+            float dot = 0.f, nn = 0.f, no = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const float a0 = __uint_as_float(nw4[t] << 16), a1 = __uint_as_float(nw4[t] & 0xffff0000u);
+              const float b0 = __uint_as_float(ow4[t] << 16), b1 = __uint_as_float(ow4[t] & 0xffff0000u);
+              if (ep->metric == 0) {
+                dot += a0 * b0; nn += a0 * a0; no += b0 * b0;
+                dot += a1 * b1; nn += a1 * a1; no += b1 * b1;
+              } else {
+                const float d0 = a0 - b0, d1 = a1 - b1;
+                dot += d0 * d0;
+                dot += d1 * d1;
+              }
+            }
+            // the eight lanes of a row: pairs, quads, then the two quads
+            dot += dpp_xor1(dot); nn += dpp_xor1(nn); no += dpp_xor1(no);
+            dot += dpp_xor2(dot); nn += dpp_xor2(nn); no += dpp_xor2(no);
+            dot += dpp_half_mirror(dot); nn += dpp_half_mirror(nn); no += dpp_half_mirror(no);
+            if (sidx >= 0 && ch == 0) {
+              ep->part[(static_cast<size_t>(0) * n_ct + ct) * ep->part_stride + sidx] = dot;
+              ep->part[(static_cast<size_t>(1) * n_ct + ct) * ep->part_stride + sidx] = nn;
+              ep->part[(static_cast<size_t>(2) * n_ct + ct) * ep->part_stride + sidx] = no;
+            }
+          }
+          if (m0 + r < M)
+            *reinterpret_cast<uint4*>(ep->cache + static_cast<size_t>(crow) * N + n0 + wn * 64 + ch * 8) = nv;
+        } else if (m0 + r < M) {
+          bf16_t* dst = is_q ? ep->q_out + static_cast<size_t>(m0 + r) * N0 + head0 + run
+                             : ep->cache + static_cast<size_t>(crow) * ep->d_kv + (head0 - N0) + run;
+          *reinterpret_cast<uint4*>(dst) = nv;
+        }
+      }
+      // ... and the loads before the next block's stores
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    return;
+  }
   if (PAIR) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -507,6 +710,33 @@ __global__ __launch_bounds__(256) void k_gemm_mid(const bf16_t* __restrict__ A, 
                                                   const bf16_t* __restrict__ W1, int N0, int N,
                                                   int K, int k_per_slice, float* __restrict__ C) {
   gemm_lds_body<2, 2, 4, 4>(A, lda, rows, M, W0, W1, N0, N, K, k_per_slice, C);
+}
+
+// Tile kernels that finish the step's work in their epilogue (single slice): V-verify and Q | K
+// with RoPE (see EPI above).
+__global__ __launch_bounds__(512) void k_gemm_fat_vverify(const bf16_t* __restrict__ A, int lda, int M,
+                                                          const bf16_t* __restrict__ W, int N, int K,
+                                                          TileEpilogue ep) {
+  gemm_lds_body<2, 4, 8, 4, 0, 1>(A, lda, nullptr, M, W, nullptr, N, N, K, K, nullptr, nullptr, &ep);
+}
+__global__ __launch_bounds__(256) void k_gemm_mid_vverify(const bf16_t* __restrict__ A, int lda, int M,
+                                                          const bf16_t* __restrict__ W, int N, int K,
+                                                          TileEpilogue ep) {
+  gemm_lds_body<2, 2, 4, 4, 0, 1>(A, lda, nullptr, M, W, nullptr, N, N, K, K, nullptr, nullptr, &ep);
+}
+__global__ __launch_bounds__(512) void k_gemm_fat_qk(const bf16_t* __restrict__ A, int lda,
+                                                     const int* __restrict__ rows, int M,
+                                                     const bf16_t* __restrict__ W0,
+                                                     const bf16_t* __restrict__ W1, int N0, int N, int K,
+                                                     TileEpilogue ep) {
+  gemm_lds_body<2, 4, 8, 4, 0, 2>(A, lda, rows, M, W0, W1, N0, N, K, K, nullptr, nullptr, &ep);
+}
+__global__ __launch_bounds__(256) void k_gemm_mid_qk(const bf16_t* __restrict__ A, int lda,
+                                                     const int* __restrict__ rows, int M,
+                                                     const bf16_t* __restrict__ W0,
+                                                     const bf16_t* __restrict__ W1, int N0, int N, int K,
+                                                     TileEpilogue ep) {
+  gemm_lds_body<2, 2, 4, 4, 0, 2>(A, lda, rows, M, W0, W1, N0, N, K, K, nullptr, nullptr, &ep);
 }
 
 // fused gate/up + SwiGLU for many rows: N is the FFN width, grid.x = N / 128 (fat) or N / 64 (mid)
@@ -847,6 +1077,69 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
     default: if (KC == 256) DLLMC_GD(4, 256, 1); else DLLMC_GD(4, 128, 1); break;
   }
 #undef DLLMC_GD
+  return true;
+}
+
+// Which tile kernel finishes a launch of M rows x N columns in one slice: 2 = 256 x 256, 1 = 128 x
+// 128, 0 = neither (the launch would leave more than a quarter of the CUs without a workgroup, or
+// the shape does not fit the tiles).
+static int direct_tile_kind(int M, int N, int N0, int K) {
+  if (K % kFatK) return 0;
+  const int cus = 256;
+  if (M >= g_tune.fat_min_m && N % kFatN == 0 && N0 % kFatN == 0 &&
+      ((M + kFatM - 1) / kFatM) * (N / kFatN) >= 3 * cus / 4)
+    return 2;
+  if (M >= g_tune.tile_min_m && N % kMidN == 0 && N0 % kMidN == 0 &&
+      ((M + kMidM - 1) / kMidM) * (N / kMidN) >= 3 * cus / 4)
+    return 1;
+  return 0;
+}
+
+bool launch_gemm_vverify_tiles(int dtype, const void* A, int lda, int M, int first, int per_seq, int n,
+                               int L_p, const void* W, int N, int K, void* v_cache, float* part,
+                               int part_stride, int metric, const int* rmap, hipStream_t st) {
+  if (M <= 0) return true;
+  if (dtype != 1 || per_seq <= 0 || lda % 8 || !aligned16(A) || !aligned16(W)) return false;
+  const int kind = direct_tile_kind(M, N, N, K);
+  if (kind == 0) return false;
+  TileEpilogue ep{};
+  ep.first = first; ep.per_seq = per_seq; ep.n = n; ep.L_p = L_p;
+  ep.cache = static_cast<bf16_t*>(v_cache);
+  ep.part = part; ep.part_stride = part_stride; ep.metric = metric; ep.rmap = rmap;
+  t_last_stream = false;
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w = static_cast<const bf16_t*>(W);
+  if (kind == 2)
+    hipLaunchKernelGGL(k_gemm_fat_vverify, dim3(N / kFatN, (M + kFatM - 1) / kFatM, 1), dim3(512), 0, st, a,
+                       lda, M, w, N, K, ep);
+  else
+    hipLaunchKernelGGL(k_gemm_mid_vverify, dim3(N / kMidN, (M + kMidM - 1) / kMidM, 1), dim3(256), 0, st, a,
+                       lda, M, w, N, K, ep);
+  return true;
+}
+
+bool launch_gemm_qk_tiles(int dtype, const void* A, int lda, const int* rows, int M, const void* wq,
+                          const void* w2, int d_q, int d_kv, int d_h, int K, const float2* rope_tab,
+                          int n, void* q_out, void* cache, bool rope_second, const int* rmap,
+                          hipStream_t st) {
+  if (M <= 0) return true;
+  if (dtype != 1 || d_h != 128 || lda % 8 || !aligned16(A) || !aligned16(wq) || !aligned16(w2)) return false;
+  const int N = d_q + d_kv;
+  const int kind = direct_tile_kind(M, N, d_q, K);
+  if (kind == 0) return false;
+  TileEpilogue ep{};
+  ep.n = n; ep.cache = static_cast<bf16_t*>(cache); ep.rmap = rmap; ep.tab = rope_tab;
+  ep.q_out = static_cast<bf16_t*>(q_out); ep.d_kv = d_kv; ep.rope_second = rope_second ? 1 : 0;
+  t_last_stream = false;
+  const bf16_t* a = static_cast<const bf16_t*>(A);
+  const bf16_t* w0 = static_cast<const bf16_t*>(wq);
+  const bf16_t* w1 = static_cast<const bf16_t*>(w2);
+  if (kind == 2)
+    hipLaunchKernelGGL(k_gemm_fat_qk, dim3(N / kFatN, (M + kFatM - 1) / kFatM, 1), dim3(512), 0, st, a, lda,
+                       rows, M, w0, w1, d_q, N, K, ep);
+  else
+    hipLaunchKernelGGL(k_gemm_mid_qk, dim3(N / kMidN, (M + kMidM - 1) / kMidM, 1), dim3(256), 0, st, a, lda,
+                       rows, M, w0, w1, d_q, N, K, ep);
   return true;
 }
 

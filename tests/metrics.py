@@ -36,3 +36,17 @@ def maxabs(got: np.ndarray, want: np.ndarray) -> float:
 
 def all_three(got: np.ndarray, want: np.ndarray) -> dict:
     return {"frob": frob(got, want), "row": row(got, want), "maxabs": maxabs(got, want)}
+
+
+def worst_element(got: np.ndarray, want: np.ndarray, count: int = 8):
+    """[(index, got, want)] of the `count` elements with the largest absolute differences (for
+    failure messages)."""
+    want = np.asarray(want, dtype=np.float64)
+    g = np.asarray(got, dtype=np.float64)
+    diff = np.abs(g - want).ravel()
+    top = np.argsort(diff)[::-1][:count]
+    out = []
+    for t in top:
+        idx = np.unravel_index(int(t), want.shape)
+        out.append((tuple(int(i) for i in idx), float(g[idx]), float(want[idx])))
+    return out

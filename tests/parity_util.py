@@ -134,7 +134,8 @@ def check_tensor(stats: ParityStats, cfg, what: str, got: np.ndarray, want: np.n
     for k in ("frob", "row", "maxabs"):
         stats.worst_over_bar = max(stats.worst_over_bar, d[k] / bar[k])
         assert d[k] <= bar[k], (f"{what}: {k} distance {d[k]:.3e} above its bar {bar[k]:.3e} "
-                                f"(oracle-only floor {entry[k]:.3e})")
+                                f"(oracle-only floor {entry[k]:.3e}); largest difference at "
+                                f"(index, got, want) = {MT.worst_element(got, want)}")
     stats.worst_row = max(stats.worst_row, d["row"])
     stats.worst_maxabs = max(stats.worst_maxabs, d["maxabs"])
     return d

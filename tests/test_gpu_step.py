@@ -465,3 +465,42 @@ def test_distance_under_both_readings_of_the_bf16_rounding_points(cfg):
           f"{caches['bf16_cache']:.3e}")
     assert worst["bf16"] <= 2e-2 and worst["bf16_cache"] <= 2e-2
     gpu.close()
+
+
+def test_tile_kernels_agree_with_the_streaming_kernels_over_many_launches():
+    """One LLaDA-8B-width layer, every step a full refresh (768 rows: the 128 x 128 LDS-direct tile
+    kernels, V-verify and Q|K RoPE finished in their epilogues), against a context created with the
+    tile kernels switched off (streaming kernels, split contraction, row kernels).  Same inputs, so
+    the caches may differ by rounding flips only.  A fragment read overtaken by the next load into
+    its LDS stage corrupts one 64-wide step of a 16-row block (about 0.2 absolute on K) in a few
+    launches per hundred: 120 launches of every projection."""
+    cfg = I.CONFIGS["llada8b"].replace(T=1, K_p=1, K_r=1)
+    ws = I.device_weights(cfg)
+    n = cfg.L_p + cfg.L_r
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    mk = lambda: binding.CachedDenoiser(
+        n_layers=cfg.T, d_model=cfg.d, n_q_heads=cfg.H_q, n_kv_heads=cfg.H_kv, head_dim=cfg.d_h,
+        d_ffn=cfg.m, batch=cfg.B, dtype=cfg.dtype, weights=ws, L_p=cfg.L_p, L_r=cfg.L_r, rho=cfg.rho,
+        K_p=cfg.K_p, K_r=cfg.K_r, rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta)
+    tiles = mk()
+    binding.set_gemm_tuning(tile_min_m=1 << 20)
+    try:
+        stream = mk()
+    finally:
+        binding.set_gemm_tuning(tile_min_m=192)
+    worst = {}
+    for i in range(120):
+        hid = torch.randn(cfg.B, n, cfg.d, device="cuda", generator=gen).to(torch.bfloat16)
+        tiles.step(hid, i)
+        stream.step(hid, i)
+        torch.cuda.synchronize()
+        for which, name in enumerate(("K", "V", "AttnOut", "FFNOut")):
+            a = tiles.read_cache(0, which).float()
+            c = stream.read_cache(0, which).float()
+            dist = float((a - c).abs().max() / c.pow(2).mean().sqrt())
+            worst[name] = max(worst.get(name, 0.0), dist)
+            assert dist <= 0.08, f"step {i} cache {name}: max |difference| / rms = {dist:.3f}"
+    print(f"[tile vs streaming] worst max|d|/rms over 120 launches: {worst}")
+    tiles.close()
+    stream.close()
