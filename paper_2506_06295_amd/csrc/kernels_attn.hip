@@ -126,7 +126,7 @@ __device__ __forceinline__ void attn_block(const bf16x8 (&kf)[2][4], const bf16x
   // The accumulators are rescaled only in the blocks in which some query's maximum moved
   // (wavefront-uniform test): with alpha == 1 for every lane the multiplications change nothing.
   if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-    const float alpha = exp2f(m_run - m_use);  // 0 while nothing has been seen yet
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);  // 0 while nothing has been seen yet
     l_run *= alpha;
     m_run = m_new;
 #pragma unroll
@@ -139,15 +139,20 @@ __device__ __forceinline__ void attn_block(const bf16x8 (&kf)[2][4], const bf16x
   }
   // probabilities as a bf16 pair (high part + remainder): the second product then carries
   // ~16 bits of each probability instead of 8
+  // (the hardware's 2^x as it is: the arguments are <= 0, and results below the normal range, which
+  // it flushes to zero, are far below anything a bf16 pair can carry)
   float psum = 0.f;
   bf16x8 pf, pl;
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    const float e = exp2f(fmaf(p[t], sl2e, -m_use));
-    psum += e;
-    const __bf16 hi = static_cast<__bf16>(e);
-    pf[t] = hi;
-    pl[t] = static_cast<__bf16>(e - static_cast<float>(hi));
+  for (int t = 0; t < 8; t += 2) {
+    const float e0 = __builtin_amdgcn_exp2f(fmaf(p[t], sl2e, -m_use));
+    const float e1 = __builtin_amdgcn_exp2f(fmaf(p[t + 1], sl2e, -m_use));
+    psum += e0;
+    psum += e1;
+    const uint32_t hi = pack_bf16x2(e0, e1);
+    reinterpret_cast<uint32_t*>(&pf)[t / 2] = hi;
+    reinterpret_cast<uint32_t*>(&pl)[t / 2] =
+        pack_bf16x2(e0 - __uint_as_float(hi << 16), e1 - __uint_as_float(hi & 0xffff0000u));
   }
   l_run += psum;
   // O^T[dim][query] += V^T[dim][key] * P^T[key][query]
@@ -497,6 +502,322 @@ __global__ __launch_bounds__(256) void k_attn_walk(const bf16_t* __restrict__ q,
   attn_walk_body<PAGED>(q, Mq, kc, vc, n, H_q, H_kv, KS, out, part, rmap);
 }
 
+// ---- many queries --------------------------------------------------------------------
+// k_attn_tile: refresh steps and batched sequences, where a (sequence, head) has hundreds of
+// queries and the work is bound by the matrix cores, the LDS and the softmax arithmetic rather
+// than by the K/V stream.  Against k_attn_walk: a wavefront owns 32 queries (two 16-query
+// column blocks), so every K and V fragment read from LDS feeds two MFMAs; blocks are 64 keys
+// (one barrier per 64 keys instead of two per 32); and V is never transposed through LDS: the
+// A operand of O^T += V^T P^T (lane: one dim, eight keys) comes straight out of the row-major V
+// tile with ds_read_b64_tr_b16.  That instruction works on groups of 16 lanes: lane 4t + q of a
+// group passes the address of four consecutive 16-bit elements -- elements 4q .. 4q+3 of row t of
+// a 4 x 16 block -- and lane i of the group receives element i of rows 0..3 (layout checked on the
+// hardware).  Here a group's rows are the keys 4*lg .. 4*lg+3 of a 16-key sub-block and the 16
+// elements a dim block, so lane (ln, lg) gets keys 4*lg .. +3 at dim db*16 + ln: with two such reads
+// (sub-blocks 2h and 2h+1) exactly the keys whose probabilities the lane holds after the first
+// product.  Two LDS stages of K tile + V tile (64 KB, two workgroups per CU); the tiles arrive by
+// global_load_lds with slot = chunk ^ (key % 16) for both, which keeps the K fragment reads (16
+// keys, one chunk each) and the transposing reads (16 keys x 32 bytes) spread over all banks.
+// Workgroup order of k_attn_tile: a "group" is everything that reads the same K and V rows -- the
+// query tiles of all query heads of one KV head, for one sequence and key range.  Groups go to the
+// XCDs round-robin and an XCD works through its groups one after the other, so the group's K/V
+// blocks are fetched into that XCD's L2 once and then hit by its other workgroups (with the tiles
+// of a head dealt over all XCDs, every XCD streams every head's keys: 2.7 GB from beyond L2 for the
+// 4608-row refresh, 36 times the K/V cache).  Groups beyond the last multiple of 8 are walked in
+// launch order.
+__device__ __forceinline__ AttnWork attn_work_tile(int qt, int H_q, int H_kv, int KS) {
+  const int G = H_q / H_kv;
+  const int W = G * qt;  // workgroups per group
+  const int n_groups = gridDim.x / W;
+  const int lin = blockIdx.x;
+  const int n8 = n_groups & ~7;
+  int group, w;
+  if (lin < n8 * W) {
+    const int xcd = lin & 7, idx = lin >> 3;
+    group = (idx / W) * 8 + xcd;
+    w = idx % W;
+  } else {
+    const int rest = lin - n8 * W;
+    group = n8 + rest / W;
+    w = rest % W;
+  }
+  // group = (b * KS + ks) * H_kv + kvh;  w = j * qt + qtile
+  AttnWork r;
+  r.qtile = w % qt;
+  const int kvh = group % H_kv;
+  const int z = group / H_kv;
+  r.b = z / KS;
+  r.ks = z % KS;
+  r.a = kvh * G + w / qt;
+  return r;
+}
+
+constexpr int kTQ = 128;  // queries per workgroup
+constexpr int kTK = 64;   // keys per block
+constexpr float kLazy = 8.0f;
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+
+template <bool PAGED>
+__device__ __forceinline__ void attn_tile_body(const bf16_t* __restrict__ q, int Mq,
+                                               const bf16_t* __restrict__ kc,
+                                               const bf16_t* __restrict__ vc, int n, int H_q,
+                                               int H_kv, int KS, bf16_t* __restrict__ out,
+                                               float* __restrict__ part,
+                                               const int* __restrict__ rmap) {
+  // [stage][K tile, V tile][64 keys][16 slots of 16 bytes]
+  __shared__ __attribute__((aligned(1024))) uint4 tiles[2][2][kTK * 16];
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const AttnWork wk = attn_work_tile((Mq + kTQ - 1) / kTQ, H_q, H_kv, KS);
+  const int a = wk.a, b = wk.b, ks = wk.ks;
+  const int d_q = H_q * kDH, d_kv = H_kv * kDH;
+  const int kv = a / (H_q / H_kv);
+  const int i0 = wk.qtile * kTQ + wave * 32;  // first query of this wavefront
+
+  const bf16_t* K = kc + kv * kDH;
+  const bf16_t* V = vc + kv * kDH;
+  const int seq0 = b * n;
+
+  // Q fragments of the two query blocks: lane (query ln, group lg) holds dims 32c + 8lg .. +8
+  bf16x8 qf[2][4];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    int qi = i0 + qb * 16 + ln;
+    if (qi >= Mq) qi = Mq - 1;  // padded queries compute a duplicate that is never stored
+    const bf16_t* qr = q + (static_cast<size_t>(b) * Mq + qi) * d_q + a * kDH + lg * 8;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) qf[qb][c] = *reinterpret_cast<const bf16x8*>(qr + c * 32);
+  }
+
+  const float sl2e = 1.4426950408889634f / sqrtf(static_cast<float>(kDH));
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  f32x4 o_acc[2][8];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int db = 0; db < 8; ++db) o_acc[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nblk = (n + kTK - 1) / kTK;
+  const int per = (nblk + KS - 1) / KS;
+  const int blk0 = ks * per;
+  const int blk1 = min(nblk, blk0 + per);
+  const int nb = blk1 - blk0;
+
+  if (nb > 0) {
+    // loader: a tile is 16 wavefront instructions of 4 keys x 256 bytes; wavefront w issues
+    // instructions 4w .. 4w+3 of the K and of the V tile.  Lane l: key 4q + l/16, slot l%16.
+    int lkey[4], chunk[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lkey[j] = 4 * (4 * wave + j) + lane / 16;
+      chunk[j] = (lane % 16) ^ (lkey[j] % 16);
+    }
+    auto rows_of = [&](int blk, int (&cr)[4]) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int kr = blk * kTK + lkey[j];
+        if (kr >= n) kr = n - 1;  // masked in the scores; any finite value will do
+        cr[j] = PAGED ? rmap[seq0 + kr] : seq0 + kr;
+      }
+    };
+    auto issue = [&](const int (&cr)[4], int stage) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t row = static_cast<size_t>(cr[j]) * d_kv;
+        __builtin_amdgcn_global_load_lds(K + row + chunk[j] * 8, &tiles[stage][0][(4 * wave + j) * 64], 16,
+                                         0, 0);
+        __builtin_amdgcn_global_load_lds(V + row + chunk[j] * 8, &tiles[stage][1][(4 * wave + j) * 64], 16,
+                                         0, 0);
+      }
+    };
+    // flat layout: a block's rows are 64 rows further on than the previous block's, so the loads
+    // take fixed per-lane pointers plus one scalar offset (a block that sticks out of the sequence
+    // goes the general way, with its rows clamped)
+    const bf16_t* kbase[4];
+    const bf16_t* vbase[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const size_t row = static_cast<size_t>(seq0 + blk0 * kTK + lkey[j]) * d_kv;  // may lie past the end: unused then
+      kbase[j] = K + row + chunk[j] * 8;
+      vbase[j] = V + row + chunk[j] * 8;
+    }
+    auto issue_block = [&](int blk, const int (&cr)[4], int stage) {
+      if (PAGED || (blk + 1) * kTK > n) {
+        issue(cr, stage);
+      } else {
+        const size_t off = static_cast<size_t>(blk - blk0) * kTK * d_kv;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          __builtin_amdgcn_global_load_lds(kbase[j] + off, &tiles[stage][0][(4 * wave + j) * 64], 16, 0, 0);
+          __builtin_amdgcn_global_load_lds(vbase[j] + off, &tiles[stage][1][(4 * wave + j) * 64], 16, 0, 0);
+        }
+      }
+    };
+    int cr_next[4];
+    rows_of(blk0, cr_next);
+    issue_block(blk0, cr_next, 0);
+    rows_of(min(blk0 + 1, blk1 - 1), cr_next);
+
+    // transposing reads: as lane 4t + q of its group this lane names key row 4*lg + t of a 16-key
+    // sub-block and dims 4q .. 4q+3 of a dim block; byte offset inside a V tile for dim block db,
+    // sub-block 0 (a sub-block further on is 16 rows = 4096 bytes further)
+    const int tt = ln / 4, tq = ln % 4;
+    const int krow = 4 * lg + tt;  // = key % 16
+    int voff[8];
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+      voff[db] = (krow * 16 + ((2 * db + tq / 2) ^ krow)) * 16 + (tq % 2) * 8;
+
+    for (int i = 0; i < nb; ++i) {
+      const int stage = i & 1;
+      // this wavefront's loads of block i have landed and its LDS reads of block i - 1 are
+      // complete; behind the barrier that holds for everybody, and the other stage is free
+      wait_vmcnt_lds<0>();
+      __builtin_amdgcn_s_barrier();
+      if (i + 1 < nb) {
+        const int cr_use[4] = {cr_next[0], cr_next[1], cr_next[2], cr_next[3]};
+        issue_block(blk0 + i + 1, cr_use, stage ^ 1);
+        rows_of(min(blk0 + i + 2, blk1 - 1), cr_next);
+      }
+      const uint4* kt = tiles[stage][0];
+      const char* vt = reinterpret_cast<const char*>(tiles[stage][1]);
+      const int key0 = (blk0 + i) * kTK;
+      // scores S^T = K Q^T: lane holds keys key0 + sb*16 + 4*lg + e of query ln (per query block)
+      f32x4 st[4][2];
+#pragma unroll
+      for (int sb = 0; sb < 4; ++sb) {
+        bf16x8 kf[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          kf[c] = __builtin_bit_cast(bf16x8, kt[(sb * 16 + ln) * 16 + ((4 * c + lg) ^ ln)]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[c], qf[qb][c], acc, 0, 0, 0);
+          st[sb][qb] = acc;
+        }
+      }
+      // Running softmax (base 2) per query block.  First the maxima of both blocks and the rare
+      // rescaling (behind a wavefront-uniform branch), then exponentials and the second product in
+      // one straight run of code, so that the MFMAs of one query block can be scheduled under the
+      // exponentials of the other.
+      if (key0 + kTK > n) {  // wavefront-uniform: the block sticks out of the sequence
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (key0 + sb * 16 + 4 * lg + e >= n) st[sb][0][e] = st[sb][1][e] = -INFINITY;
+      }
+      float m_use[2], m_new[2];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[sb][qb][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // The reference point of the exponentials follows the running maximum lazily: it moves only
+        // when the maximum has grown by more than kLazy (base-2 units) since it was last set, so
+        // probabilities reach at most 2^kLazy (harmless in float32 sums and in a bf16 pair) and the
+        // result is the same quotient.  With 32 queries per wavefront some maximum moves in most
+        // blocks; by more than kLazy hardly ever after the first ones.
+        const float mb = mx * sl2e;
+        m_new[qb] = mb > m_run[qb] + kLazy ? mb : m_run[qb];
+        m_use[qb] = m_new[qb] == -INFINITY ? 0.f : m_new[qb];
+      }
+      // the accumulators are rescaled only in the blocks in which some query's reference moved
+      if (__builtin_amdgcn_ballot_w64(m_new[0] != m_run[0] || m_new[1] != m_run[1]) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          // 1 where nothing moved, 0 while nothing has been seen yet
+          const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_use[qb]);
+          l_run[qb] *= alpha;
+          m_run[qb] = m_new[qb];
+#pragma unroll
+          for (int db = 0; db < 8; ++db) {
+            o_acc[qb][db][0] *= alpha;
+            o_acc[qb][db][1] *= alpha;
+            o_acc[qb][db][2] *= alpha;
+            o_acc[qb][db][3] *= alpha;
+          }
+        }
+      }
+      // Probabilities as a bf16 pair (high part + remainder: as single bf16 values they cost 11 % of
+      // the step's distance from the float64 evaluation at full depth, more than the 2e-2 budget
+      // has left), laid out as the B operand of the second product: MFMA k-slot 8*lg + t of half h is key
+      // key0 + (2h + t/4)*16 + 4*lg + t%4.  (The hardware's 2^x as it is: the arguments are <= 0, and
+      // results below the normal range, which it flushes to zero, are far below anything a bf16
+      // probability can carry.)
+      // The exponentials of the block's second 32 keys are dealt out between the MFMAs of its first
+      // 32 (eight pieces of four probabilities, one per dim block).  That buys little here: on this
+      // chip an MFMA with VALU instructions behind it takes its 16 cycles plus most of theirs
+      // (measured: MFMA alone 16.9 cycles, with 4 v_fma 34.6, with 8 43.4 per MFMA at four
+      // wavefronts per SIMD), so the block costs about the sum of its matrix and vector cycles and
+      // what counts is the number of vector instructions per key.
+      bf16x8 pf[2][2], pl[2][2];
+      float psum[2] = {0.f, 0.f};
+      auto exp_piece = [&](int qb, int sb, int e) {  // probabilities e, e+1 of sub-block sb
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(st[sb][qb][e], sl2e, -m_use[qb]));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(st[sb][qb][e + 1], sl2e, -m_use[qb]));
+        psum[qb] += e0;
+        psum[qb] += e1;
+        const uint32_t hi = pack_bf16x2(e0, e1);
+        reinterpret_cast<uint32_t*>(&pf[qb][sb / 2])[(sb % 2) * 2 + e / 2] = hi;
+        reinterpret_cast<uint32_t*>(&pl[qb][sb / 2])[(sb % 2) * 2 + e / 2] =
+            pack_bf16x2(e0 - __uint_as_float(hi << 16), e1 - __uint_as_float(hi & 0xffff0000u));
+      };
+      // O^T[dim][query] += V^T[dim][key] P^T[key][query] for dim block db and key half h
+      auto pv_piece = [&](int db, int h) {
+        typedef v4i16_t __attribute__((address_space(3))) * lds_v4;
+        const v4i16_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vt + voff[db] + (2 * h) * 4096));
+        const v4i16_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vt + voff[db] + (2 * h + 1) * 4096));
+        typedef short v8i16_t __attribute__((ext_vector_type(8)));
+        const v8i16_t both = {r0[0], r0[1], r0[2], r0[3], r1[0], r1[1], r1[2], r1[3]};
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          o_acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qb][h], o_acc[qb][db], 0, 0, 0);
+          o_acc[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pl[qb][h], o_acc[qb][db], 0, 0, 0);
+        }
+      };
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int e = 0; e < 4; e += 2) exp_piece(qb, sb, e);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < 8; ++db) {
+        pv_piece(db, 0);
+        exp_piece(db / 4, 2 + (db / 2) % 2, (db % 2) * 2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int db = 0; db < 8; ++db) pv_piece(db, 1);
+      l_run[0] += psum[0];
+      l_run[1] += psum[1];
+    }
+  }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+    attn_finish(o_acc[qb], m_run[qb], l_run[qb], i0 + qb * 16 + ln, Mq, b, a, ks, KS, H_q, lg, out, part);
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(256, 2) void k_attn_tile(const bf16_t* __restrict__ q, int Mq,
+                                                      const bf16_t* __restrict__ kc,
+                                                      const bf16_t* __restrict__ vc, int n, int H_q,
+                                                      int H_kv, int KS, bf16_t* __restrict__ out,
+                                                      float* __restrict__ part,
+                                                      const int* __restrict__ rmap) {
+  attn_tile_body<PAGED>(q, Mq, kc, vc, n, H_q, H_kv, KS, out, part, rmap);
+}
+
 // out[query][head][:] = sum_r O_r 2^(m_r - M) / sum_r l_r 2^(m_r - M), in key-range order.
 // One wavefront per (query, head), two dims per lane.
 template <int SLOTS>
@@ -552,6 +873,28 @@ void launch_attention(int dtype, const void* q, int B, int Mq, const void* k_cac
     const bf16_t* kk = static_cast<const bf16_t*>(k_cache);
     const bf16_t* vv = static_cast<const bf16_t*>(v_cache);
     bf16_t* oo = static_cast<bf16_t*>(out);
+    if (Mq >= kTQ) {
+      // many queries per (sequence, head): 128-query tiles; the keys are split only when the
+      // queries alone would leave at least half of the CUs without a workgroup
+      const int base128 = B * ((Mq + kTQ - 1) / kTQ) * H_q;
+      const int nblk64 = (n + kTK - 1) / kTK;
+      int KS = 1;
+      if (scratch != nullptr && 2 * base128 <= 256) {
+        KS = 256 / base128;
+        if (KS > 8) KS = 8;
+        if (KS > nblk64 / 2) KS = nblk64 / 2 > 0 ? nblk64 / 2 : 1;
+      }
+      const dim3 grid(base128 * KS);
+      if (rmap)
+        hipLaunchKernelGGL(k_attn_tile<true>, grid, dim3(256), 0, st, qq, Mq, kk, vv, n, H_q, H_kv, KS, oo,
+                           scratch, rmap);
+      else
+        hipLaunchKernelGGL(k_attn_tile<false>, grid, dim3(256), 0, st, qq, Mq, kk, vv, n, H_q, H_kv, KS, oo,
+                           scratch, rmap);
+      if (KS > 1)
+        hipLaunchKernelGGL(k_attn_merge<8>, dim3(B * Mq * H_q), dim3(64), 0, st, scratch, KS, oo);
+      return;
+    }
     const int qt = (Mq + kQT - 1) / kQT;
     const int base = B * qt * H_q;  // workgroups without splitting the keys
     const int nblk = (n + 31) / 32;

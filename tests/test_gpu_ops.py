@@ -197,7 +197,11 @@ def test_vverify_scores_and_cache_overwrite(dtype, rows, d, d_kv):
     ("bf16", 1, 64, 768, 4, 4, 128),     # adaptive-step shape: key range split over wavefronts
     ("bf16", 2, 20, 176, 8, 8, 128),     # ragged queries and keys
     ("bf16", 1, 51, 333, 7, 1, 128),     # grouped KV heads
-    ("bf16", 3, 200, 200, 28, 4, 128),   # many queries: query-tiled variant
+    ("bf16", 3, 200, 200, 28, 4, 128),   # many queries: 128-query tiles, second tile and last key block ragged
+    ("bf16", 1, 256, 768, 4, 4, 128),    # 128-query tiles with the keys split six ways and merged
+    ("bf16", 2, 130, 1000, 8, 2, 128),   # the same with grouped KV heads, two queries in the second tile
+    ("bf16", 1, 128, 64, 2, 2, 128),     # exactly one tile and one key block
+    ("bf16", 1, 300, 40, 2, 1, 128),     # 128-query tiles, fewer keys than one block
     ("bf16", 1, 40, 2500, 2, 2, 128),    # long key ranges: 16 ranges of 5 blocks, the last one shorter
     ("bf16", 2, 70, 1100, 8, 2, 128),    # the same with grouped KV heads and two query tiles
     ("bf16", 1, 7, 5, 2, 2, 128),        # fewer keys than one block
