@@ -107,6 +107,36 @@ __device__ __forceinline__ void xcd_tile_map(int& col_tile, int& row_tile) {
     }
   }
 }
+// Tile order of the LDS-direct tile kernels.  What matters for them is how many DIFFERENT operand
+// blocks the workgroups that run at the same time on one XCD pull into its L2: 32 workgroups (one
+// per CU) that share one weight tile and differ in their activation rows -- what dealing column
+// tiles to the XCDs round-robin gives a tall problem -- fetch 33 blocks per step between them, all
+// but one of them used once, and a 12288-row projection then reads its activations from memory
+// once per column tile (1.7 GB for 130 MB of operands) and runs at the speed of that traffic.  Here
+// the tiles are put in an order of bands of kBand row tiles, walked column by column with the rows
+// of the band innermost, and every XCD takes a contiguous piece of that order: its concurrent
+// workgroups then form a patch of about kBand x (32 / kBand) tiles, 12 blocks per step for 32
+// tiles.  The map is a bijection of the grid for any mt, nt.
+constexpr int kBand = 8;
+__device__ __forceinline__ void xcd_tile_map_blocked(int& col_tile, int& row_tile) {
+  const int nt = gridDim.x, mt = gridDim.y;
+  const int T = nt * mt;
+  const int lin = blockIdx.x + nt * blockIdx.y;
+  if (T < 16) {  // nothing to arrange
+    col_tile = blockIdx.x;
+    row_tile = blockIdx.y;
+    return;
+  }
+  // XCD x runs the workgroups lin = x, x + 8, ...: (T - x + 7) / 8 of them; its piece of the order
+  // starts where the pieces of the XCDs before it end
+  const int xcd = lin & 7, slot = lin >> 3;
+  const int g = xcd * (T >> 3) + min(xcd, T & 7) + slot;
+  const int band = g / (kBand * nt);
+  const int rows_in_band = min(kBand, mt - band * kBand);
+  const int within = g - band * kBand * nt;
+  row_tile = band * kBand + within % rows_in_band;
+  col_tile = within / rows_in_band;
+}
 // s_waitcnt with only vmcnt set: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));

@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     const bf16_t* __restrict__ vc, int n, int H_q, int H_kv, int KS, bf16_t* __restrict__ out,
     float* __restrict__ part, const int* __restrict__ rmap) {
   __shared__ __attribute__((aligned(16))) bf16_t Vt[kPreload][kDH * kVtStride];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;  // scalar
   const int ln = lane % 16, lg = lane / 16;
   const AttnWork wk = attn_work((Mq + kQT - 1) / kQT, H_q, H_kv, KS);
   const int a = wk.a, b = wk.b, ks = wk.ks;
@@ -371,7 +371,7 @@ __device__ __forceinline__ void attn_walk_body(const bf16_t* __restrict__ q, int
   __shared__ __attribute__((aligned(1024))) uint4 smem[kTileVecs + kDH * kVtStrideW * 2 / 16];
   uint4 (*tiles)[2][32 * 16] = reinterpret_cast<uint4 (*)[2][32 * 16]>(smem);
   bf16_t* Vt = reinterpret_cast<bf16_t*>(smem + kTileVecs);
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;  // scalar
   const int ln = lane % 16, lg = lane / 16;
   const AttnWork wk = attn_work((Mq + kQT - 1) / kQT, H_q, H_kv, KS);
   const int a = wk.a, b = wk.b, ks = wk.ks;
@@ -566,7 +566,7 @@ __device__ __forceinline__ void attn_tile_body(const bf16_t* __restrict__ q, int
                                                const int* __restrict__ rmap) {
   // [stage][K tile, V tile][64 keys][16 slots of 16 bytes]
   __shared__ __attribute__((aligned(1024))) uint4 tiles[2][2][kTK * 16];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;  // scalar
   const int ln = lane % 16, lg = lane / 16;
   const AttnWork wk = attn_work_tile((Mq + kTQ - 1) / kTQ, H_q, H_kv, KS);
   const int a = wk.a, b = wk.b, ks = wk.ks;

@@ -183,7 +183,8 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     const int h = e / (R * CPR), r = (e / CPR) % R, c = e % CPR;
     const int m = m0 + r;
     aval[j] = ain[j] && m < M;
-    const int row = aval[j] ? (rows ? rows[m] : m) : 0;
+    const int mm = min(m, M - 1);  // chunks without a row of their own read a valid one and are zeroed
+    const int row = rows ? rows[mm] : mm;
     asrc[j] = A + static_cast<size_t>(row) * lda + kbeg + h * hlen + c * 8;
     adst[j] = h * R * LS + r * LS + (c ^ (r % 16)) * 8;
   }
@@ -198,12 +199,14 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
   for (int c = 0; c < 4; ++c) fo[c] = ((4 * c + lg) ^ ln) * 8;
 
+  // The activation chunks of the first phase: every load goes out before the first one is used
+  // (rows past M and chunks past the tile read a valid row and are zeroed or dropped afterwards --
+  // a load under "if (row < M)" is a basic block of its own, and the store that follows it then
+  // waits for it before the next load is issued: one trip to memory per chunk), and so do the
+  // first weight pieces, before the activations are waited for.
+  uint4 a0[NCH];
 #pragma unroll
-  for (int j = 0; j < NCH; ++j) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (aval[j]) v = *reinterpret_cast<const uint4*>(asrc[j] + rot * KC);
-    if (ain[j]) *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = v;
-  }
+  for (int j = 0; j < NCH; ++j) a0[j] = *reinterpret_cast<const uint4*>(asrc[j] + rot * KC);
   // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
   constexpr int NS = KC / 128;
   uint4 bn[NB][NS][4];
@@ -216,6 +219,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
         for (int c = 0; c < 4; ++c)
           bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + rot * KC + t * 128 + c * 32);
   }
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    if (!aval[j]) a0[j] = make_uint4(0u, 0u, 0u, 0u);
+    if (ain[j]) *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = a0[j];
+  }
   __syncthreads();
 
   for (int ph = 0; ph < nph; ++ph) {
@@ -225,10 +233,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     uint4 av[NCH];
     if (more) {
 #pragma unroll
-      for (int j = 0; j < NCH; ++j) {
-        av[j] = make_uint4(0u, 0u, 0u, 0u);
-        if (aval[j]) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + pn * KC);
-      }
+      for (int j = 0; j < NCH; ++j) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + pn * KC);
     }
     const bf16_t* ap = &As[ph & 1][kh][ln * LS];
     if (active) {
@@ -262,8 +267,10 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
     }
     if (more) {
 #pragma unroll
-      for (int j = 0; j < NCH; ++j)
+      for (int j = 0; j < NCH; ++j) {
+        if (!aval[j]) av[j] = make_uint4(0u, 0u, 0u, 0u);
         if (ain[j]) *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][0][adst[j]]) = av[j];
+      }
     }
     __syncthreads();
   }
@@ -385,11 +392,13 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   __shared__ __attribute__((aligned(1024))) uint4 lds_all[2 * kStage + (EPI ? 2 * BM / 4 : 0)];
   uint4 (*lds)[kStage] = reinterpret_cast<uint4 (*)[kStage]>(lds_all);
   int (*meta)[BM] = reinterpret_cast<int (*)[BM]>(lds_all + 2 * kStage);
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  // (the wavefront index as a scalar: the LDS addresses of the loads, which go through M0, are then
+  // scalar arithmetic instead of vector instructions and v_readfirstlane in every step)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int wm = wave / WN, wn = wave % WN;
   int col_tile, row_tile;
-  xcd_tile_map(col_tile, row_tile);
+  xcd_tile_map_blocked(col_tile, row_tile);
   static_assert(!PAIR || NJ % 2 == 0, "gate and up column blocks come in pairs");
   const int m0 = row_tile * BM, n0 = col_tile * (PAIR ? BN / 2 : BN);
   const int kbeg = blockIdx.z * k_per_slice;
@@ -467,7 +476,13 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   // wait for step kt (a longer window for the shorter steps) and a second barrier at the end of
   // the step protects the stage they overwrite.
   constexpr bool ONE_BARRIER = NWV == 8;
-  DLLMC_LDS_ISSUE(0, 0)
+  // The walk over the contraction index starts at a step that depends on the XCD and wraps
+  // around: the workgroups of a launch run nearly in step and their rows are a multiple of 4 KB
+  // apart, so unrotated every load in flight on the chip has the same address bits below the row
+  // pitch and the memory channels are loaded unevenly (4096 x 4096 x 16384: 959 -> 1097 TFLOP/s).
+  // The workgroups of one XCD keep a common start, they share operand blocks through its L2.
+  const int rot = (((blockIdx.x + gridDim.x * blockIdx.y) & 7) * nkt) >> 3;
+  DLLMC_LDS_ISSUE(0, rot)
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < nkt;
@@ -476,10 +491,10 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
       // complete (not merely issued: the loads below overwrite their stage)
       wait_vmcnt_lds<0>();
       __builtin_amdgcn_s_barrier();
-      if (more) DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
+      if (more) DLLMC_LDS_ISSUE(cur ^ 1, kt + 1 + rot < nkt ? kt + 1 + rot : kt + 1 + rot - nkt)
     } else {
       if (more) {
-        DLLMC_LDS_ISSUE(cur ^ 1, kt + 1)
+        DLLMC_LDS_ISSUE(cur ^ 1, kt + 1 + rot < nkt ? kt + 1 + rot : kt + 1 + rot - nkt)
         wait_vmcnt<LA + LB>();  // this wavefront's loads of step kt have landed
       } else {
         wait_vmcnt<0>();
@@ -756,6 +771,18 @@ __global__ __launch_bounds__(256) void k_gemm_mid_swiglu(const bf16_t* __restric
   gemm_lds_body<2, 2, 4, 4, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
 }
 
+// 256 rows x (96 gate + 96 up) columns, 4 x 2 wavefronts of 64 x 96 each, one workgroup per CU: the
+// column count that makes whole rounds of workgroups when the 256 x (128 + 128) tiles do not
+// (1024 rows x FFN width 12288: 384 tiles of the latter are a full round and a half-empty one,
+// 512 of these are two full rounds of tiles three quarters the size).
+__global__ __launch_bounds__(512) void k_gemm_fat96_swiglu(const bf16_t* __restrict__ A, int lda,
+                                                           const int* __restrict__ rows, int M,
+                                                           const bf16_t* __restrict__ Wg,
+                                                           const bf16_t* __restrict__ Wu, int N, int K,
+                                                           bf16_t* __restrict__ U) {
+  gemm_lds_body<4, 2, 4, 6, 1>(A, lda, rows, M, Wg, Wu, N, N, K, K, nullptr, U);
+}
+
 // 256 rows x (48 gate + 48 up) columns, four wavefronts of 64 x 96 each: for up to 256 rows and
 // an FFN width that is a multiple of 48 the grid is one workgroup per 48 columns (12288 / 48 =
 // 256, one per CU), where the 128 x 128 tiles leave half of the CUs with twice the work (a
@@ -1019,9 +1046,21 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
       const bf16_t* w0 = static_cast<const bf16_t*>(w_gate);
       const bf16_t* w1 = static_cast<const bf16_t*>(w_up);
       bf16_t* uo = static_cast<bf16_t*>(u);
+      // 96-column tiles when their rounds over the CUs finish sooner (a tile's time goes with its
+      // columns; the narrower tile pulls a few per cent more operand bytes per flop)
+      bool fat96 = false;
+      if (fat && m % 96 == 0) {
+        const int mt = (M + kFatM - 1) / kFatM, cus = 256;
+        const double c128 = static_cast<double>((mt * (m / 128) + cus - 1) / cus) * 128.0;
+        const double c96 = static_cast<double>((mt * (m / 96) + cus - 1) / cus) * 96.0 * 1.05;
+        fat96 = c96 < c128;
+      }
       if (tall)
         hipLaunchKernelGGL(k_gemm_tall_swiglu, dim3(m / 48, 1, 1), dim3(256), 0, st, a, lda, rows, M,
                            w0, w1, m, K, uo);
+      else if (fat96)
+        hipLaunchKernelGGL(k_gemm_fat96_swiglu, dim3(m / 96, (M + kFatM - 1) / kFatM, 1), dim3(512), 0, st, a,
+                           lda, rows, M, w0, w1, m, K, uo);
       else if (fat)
         hipLaunchKernelGGL(k_gemm_fat_swiglu, dim3(m / (kFatN / 2), (M + kFatM - 1) / kFatM, 1),
                            dim3(512), 0, st, a, lda, rows, M, w0, w1, m, K, uo);

@@ -118,11 +118,13 @@ def test_degenerate_shapes(cfg):
 
 
 @pytest.mark.parametrize("fat_min_m", [1024, 64], ids=["mid_tiles", "fat_tiles"])
-@pytest.mark.parametrize("cfg", [MINI_LLADA, MINI_DREAM], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [MINI_LLADA, MINI_DREAM, MINI_LLADA.replace(name="mini_llada_ffn2048", m=2048)],
+                         ids=lambda c: c.name)
 def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
     """Refresh steps (hundreds of rows) run gate/up + SwiGLU fused inside the LDS-direct tile
-    kernels (128 x 128 by default, 256 x 256 when forced); MINI_DREAM's FFN width (2432 = 38 x 64)
-    fits the 128-wide pairing only, so its forced case falls back to the narrower kernel."""
+    kernels (128 x 128 by default, 256-row tiles when forced: 96 paired columns where the FFN width
+    is a multiple of 96 and that makes fewer rounds -- MINI_LLADA's 3072 --, 128 otherwise --
+    2048, and MINI_DREAM's 2432 = 19 x 128)."""
     binding.set_gemm_tuning(fat_min_m=fat_min_m)
     try:
         gpu, ora, st = run_schedule(cfg.replace(steps=4), stress=True, K_r=1)   # every step refreshes the response
@@ -498,9 +500,15 @@ def test_tile_kernels_agree_with_the_streaming_kernels_over_many_launches():
         for which, name in enumerate(("K", "V", "AttnOut", "FFNOut")):
             a = tiles.read_cache(0, which).float()
             c = stream.read_cache(0, which).float()
-            dist = float((a - c).abs().max() / c.pow(2).mean().sqrt())
-            worst[name] = max(worst.get(name, 0.0), dist)
-            assert dist <= 0.08, f"step {i} cache {name}: max |difference| / rms = {dist:.3f}"
-    print(f"[tile vs streaming] worst max|d|/rms over 120 launches: {worst}")
+            # The two paths sum in different orders, so values may round to neighbouring bf16 values
+            # (2^-7 of the value; K and V) and those flips spread a little behind the attention.  A
+            # corrupted step shifts every element of a 16-row block by about 0.2 in absolute terms.
+            rms = float(c.pow(2).mean().sqrt())
+            slack = (0.03 if which < 2 else 0.12) * rms
+            excess = float(((a - c).abs() - 0.03 * c.abs()).max()) / rms
+            worst[name] = max(worst.get(name, 0.0), excess)
+            assert excess * rms <= slack, (f"step {i} cache {name}: an element differs by {excess:.3f} rms "
+                                          f"beyond 3 % of its value")
+    print(f"[tile vs streaming] worst (|d| - 3 % of the value) / rms over 120 launches: {worst}")
     tiles.close()
     stream.close()
