@@ -80,6 +80,14 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// a pointer that is the same in every lane, re-read from lane 0 (lands in scalar registers)
+__device__ __forceinline__ const char* wave_uniform_ptr(const char* p) {
+  const uint64_t b = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b >> 32));
+  return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
 // ---- MFMA operand types, tile-to-XCD mapping, explicit waits ----------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;

@@ -336,10 +336,11 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 // contiguous bytes (64 values of the contraction index) into 1 KB of LDS in lane order, i.e.
 // LDS holds [row][8 slots of 16 bytes]; the slot of chunk c of row r is c ^ (r % 8) so that
 // the 16-byte fragment reads of 8 consecutive rows hit 8 different bank groups.  Two LDS
-// stages: the loads of step t+1 are in flight while step t is multiplied.
+// stages (128-row tiles) or five slots of one operand block (256-row tiles): later steps'
+// loads are in flight while step t is multiplied.
 // Rows beyond M read a valid row again and are dropped at the store.
 //   fat: 2 x 4 wavefronts of 128 x 64 -> 256 x 256 tile (every byte pulled from L2 feeds 128
-//        flops), 128 KB of LDS, one workgroup per CU: M >= fat_min_m.
+//        flops), all 160 KB of LDS, one workgroup per CU: M >= fat_min_m.
 //   mid: 2 x 2 wavefronts of  64 x 64 -> 128 x 128 tile, 64 KB of LDS, two workgroups per CU:
 //        enough tiles to fill the chip when M is a few hundred rows.
 constexpr int kFatM = 256, kFatN = 256, kFatK = 64;
@@ -389,9 +390,20 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   // one the compiler can no longer tell the fragment reads from the loads in flight into the
   // other stage and waits for those before every read.)
   constexpr int kStage = (BM + BN) * 8;
-  __shared__ __attribute__((aligned(1024))) uint4 lds_all[2 * kStage + (EPI ? 2 * BM / 4 : 0)];
+  // Two ways through the contraction.  Two workgroups per CU (128 x 128, four wavefronts): two
+  // stages of both operands; the loads of step kt+1 go out before the wait for step kt and a
+  // second barrier at the end of the step protects the stage they overwrite (the five-slot loop
+  // with 16 KB slots measured 3-8 % slower there).  One workgroup per CU (256-row tiles): five
+  // slots of one operand block each (all 160 KB of the CU), one barrier per step, see the main
+  // loop.
+  constexpr bool ONE_BARRIER = BM == 256;
+  constexpr int kSlot = (BM > BN ? BM : BN) * 8;
+  constexpr int kLdsTotal = ONE_BARRIER ? 5 * kSlot : 2 * kStage + (EPI ? 2 * BM / 4 : 0);
+  static_assert(kLdsTotal * sizeof(uint4) <= 160 * 1024, "LDS of one CU");
+  __shared__ __attribute__((aligned(1024))) uint4 lds_all[kLdsTotal];
   uint4 (*lds)[kStage] = reinterpret_cast<uint4 (*)[kStage]>(lds_all);
-  int (*meta)[BM] = reinterpret_cast<int (*)[BM]>(lds_all + 2 * kStage);
+  // (five slots: the table lives in the last slot, written after the main loop)
+  int (*meta)[BM] = reinterpret_cast<int (*)[BM]>(lds_all + (ONE_BARRIER ? 4 * kSlot : 2 * kStage));
   // (the wavefront index as a scalar: the LDS addresses of the loads, which go through M0, are then
   // scalar arithmetic instead of vector instructions and v_readfirstlane in every step)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
@@ -440,19 +452,26 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
   // EPI: what the epilogue needs to know about the tile's rows, looked up here so that the trips
   // to memory pass under the main loop.  EPI 1: cache row, index of the row's score (-1: not
   // scored); EPI 2: position in the sequence, cache row.
+  // (with five slots there is no room for the table during the main loop: the thread keeps its
+  // row's two entries in registers and writes them to the last slot afterwards)
+  int meta_r0 = 0, meta_r1 = 0;
   if (EPI != 0 && threadIdx.x < BM) {
     const int r = threadIdx.x;
     const int m = min(m0 + r, M - 1);
     if (EPI == 1) {
       const int seq = m / ep->per_seq, pos = ep->first + m % ep->per_seq;
       const int row = seq * ep->n + pos;
-      meta[0][r] = ep->rmap ? ep->rmap[row] : row;
-      meta[1][r] = (m0 + r < M && ep->part != nullptr && pos >= ep->L_p)
+      meta_r0 = ep->rmap ? ep->rmap[row] : row;
+      meta_r1 = (m0 + r < M && ep->part != nullptr && pos >= ep->L_p)
                                  ? seq * (ep->n - ep->L_p) + (pos - ep->L_p) : -1;
     } else {
       const int row = rows ? rows[m] : m;
-      meta[0][r] = row % ep->n;
-      meta[1][r] = ep->rmap ? ep->rmap[row] : row;
+      meta_r0 = row % ep->n;
+      meta_r1 = ep->rmap ? ep->rmap[row] : row;
+    }
+    if (!ONE_BARRIER) {
+      meta[0][r] = meta_r0;
+      meta[1][r] = meta_r1;
     }
   }
 #define DLLMC_LDS_ISSUE(stage, kt)                                                              \
@@ -469,30 +488,163 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Two ways through a step.  One workgroup per CU (the 256 x 256 tile): a single barrier,
-  // behind which everybody's loads of step kt have landed AND everybody has finished the
-  // fragment reads of step kt-1, so the loads of step kt+1 are issued right after it into the
-  // other stage.  Two workgroups per CU (128 x 128): the loads of step kt+1 go out before the
-  // wait for step kt (a longer window for the shorter steps) and a second barrier at the end of
-  // the step protects the stage they overwrite.
-  constexpr bool ONE_BARRIER = NWV == 8;
   // The walk over the contraction index starts at a step that depends on the XCD and wraps
   // around: the workgroups of a launch run nearly in step and their rows are a multiple of 4 KB
   // apart, so unrotated every load in flight on the chip has the same address bits below the row
   // pitch and the memory channels are loaded unevenly (4096 x 4096 x 16384: 959 -> 1097 TFLOP/s).
   // The workgroups of one XCD keep a common start, they share operand blocks through its L2.
   const int rot = (((blockIdx.x + gridDim.x * blockIdx.y) & 7) * nkt) >> 3;
+  auto kof = [&](int kt) { const int k = kt + rot; return (k < nkt ? k : k - nkt) * kFatK; };
+  if (ONE_BARRIER) {
+    // Five slots of one operand block (256 rows x 64 contraction values) each.  Blocks are
+    // numbered in the order they are needed, A(0), B(0), A(1), B(1), ...; block p lives in slot
+    // p % 5.  While step kt multiplies A(kt) and B(kt), A(kt+1), B(kt+1) and A(kt+2) are landing
+    // or have landed, and the barrier of step kt -- everybody has finished the fragment reads of
+    // step kt, everybody's loads up to B(kt+1) have landed -- makes room for B(kt+2) and A(kt+3):
+    // 96 KB in flight per CU instead of the 64 KB of two stages, A(kt+2) stays in flight across
+    // the barrier (the memory pipeline never drains), and the new loads go out two per MFMA unit
+    // over the following step instead of all behind the barrier, where sixteen wavefronts'
+    // worth of address work kept the matrix pipes waiting (the 256 x 256 x 64 step: 1.12 ->
+    // 1.38 PFLOP/s on 12288 x 4096 x 12288).
+    //
+    // The step's MFMAs go in units of 4 activation blocks x NJ weight blocks x 32 contraction
+    // values, and the fragments of unit u + 1 are read from LDS into a second register set while
+    // the MFMAs of unit u run: the wavefronts of a workgroup leave every barrier together, so
+    // without this they all read fragments at the same time and then all multiply, and the
+    // matrix pipes idle for an LDS round trip in front of every group of MFMAs.  The barrier
+    // sits in front of the step's last unit.
+    constexpr int AG = 4;            // activation fragments per unit
+    constexpr int UH = MI / AG;      // units per 32 contraction values
+    constexpr int NU = 2 * UH;       // units per step
+    constexpr int NL = LA + LB;      // loads per wavefront and step: B(kt+2) first, then A(kt+3)
+    static_assert(MI % AG == 0, "units of four activation blocks");
+    auto issue_a = [&](int slot, int kt, int j0, int j1) {
+      const int ko = kof(kt);
+#pragma unroll
+      for (int j = j0; j < j1; ++j)
+        __builtin_amdgcn_global_load_lds(asrc[j] + ko, &lds_all[slot * kSlot + (LA * wave + j) * 64],
+                                         16, 0, 0);
+    };
+    // Weight loads take their address as a scalar base + a 32-bit lane offset (no vector
+    // arithmetic per load): the 8 rows of one load instruction are consecutive rows of one
+    // matrix (the tile origins and the W0 | W1 boundary are multiples of 8), so the lane offset
+    // -- row lane/8, chunk (lane%8) ^ (lane/8) -- is the same for every instruction and the base
+    // is lane 0's address.  The scalar sum is re-read as a wavefront constant and the offset
+    // passes through an empty asm so that the compiler neither folds the two into per-lane
+    // 64-bit pointers outside the loop nor moves the zero-extension away from the load, either
+    // of which loses the addressing form.
+    const char* bbase[LB];
+#pragma unroll
+    for (int j = 0; j < LB; ++j) bbase[j] = wave_uniform_ptr(reinterpret_cast<const char*>(bsrc[j]));
+    const uint32_t boff =
+        static_cast<uint32_t>(reinterpret_cast<const char*>(bsrc[0]) - bbase[0]);
+    auto issue_b = [&](int slot, int kt, int j0, int j1) {
+      const int ko = kof(kt);
+#pragma unroll
+      for (int j = j0; j < j1; ++j) {
+        const char* bp = wave_uniform_ptr(bbase[j] + ko * static_cast<int>(sizeof(bf16_t)));
+        uint32_t o = boff;
+        asm volatile("" : "+v"(o));
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint4*>(bp + o),
+                                         &lds_all[slot * kSlot + (LB * wave + j) * 64], 16, 0, 0);
+      }
+    };
+    // loads [i0, i1) of the NL that the barrier of step kb makes room for (slots sa_b, sb_b of that
+    // step's operands)
+    auto issue_some = [&](int kb, int sa_b, int sb_b, int i0, int i1) {
+      const int b0 = min(i0, LB), b1 = min(i1, LB);
+      const int a0 = max(i0, LB) - LB, a1 = max(i1, LB) - LB;
+      if (b1 > b0 && kb + 2 < nkt) issue_b(sa_b, kb + 2, b0, b1);
+      if (a1 > a0 && kb + 3 < nkt) issue_a(sb_b, kb + 3, a0, a1);
+    };
+    bf16x8 af[2][AG], bf[2][NJ];
+    auto read_a = [&](int slot, int u, bf16x8 (&dst)[AG]) {
+      const uint4* la = &lds_all[slot * kSlot];
+      const int c = (u / UH) * 4 + lg;
+#pragma unroll
+      for (int i = 0; i < AG; ++i) {
+        const int r = wm * (MI * 16) + ((u % UH) * AG + i) * 16 + ln;
+        dst[i] = __builtin_bit_cast(bf16x8, la[r * 8 + (c ^ (r % 8))]);
+      }
+    };
+    auto read_b = [&](int slot, int kk, bf16x8 (&dst)[NJ]) {
+      const uint4* lb = &lds_all[slot * kSlot];
+      const int c = kk * 4 + lg;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int r = PAIR ? (j / (NJ / 2)) * (BN / 2) + wn * (NJ / 2 * 16) + (j % (NJ / 2)) * 16 + ln
+                           : wn * (NJ * 16) + j * 16 + ln;
+        dst[j] = __builtin_bit_cast(bf16x8, lb[r * 8 + (c ^ (r % 8))]);
+      }
+    };
+    issue_a(0, 0, 0, LA);
+    issue_b(1, 0, 0, LB);
+    if (nkt > 1) {
+      issue_a(2, 1, 0, LA);
+      issue_b(3, 1, 0, LB);
+    }
+    if (nkt > 2) {
+      issue_a(4, 2, 0, LA);
+      wait_vmcnt_lds<2 * LA + LB>();
+    } else if (nkt > 1) {
+      wait_vmcnt_lds<LA + LB>();
+    } else {
+      wait_vmcnt_lds<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    read_a(0, 0, af[0]);
+    read_b(1, 0, bf[0]);
+    int sa = 0;            // slot of A(kt); B(kt) is in the next one (mod 5)
+    int sap = 0, sbp = 0;  // the slots of the step before
+    for (int kt = 0; kt < nkt; ++kt) {
+      const int sb = sa + 1 < 5 ? sa + 1 : sa - 4;
+      const int sa1 = sb + 1 < 5 ? sb + 1 : sb - 4;     // A(kt+1)
+      const int sb1 = sa1 + 1 < 5 ? sa1 + 1 : sa1 - 4;  // B(kt+1)
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        // The first row of MFMAs of the unit goes first: the compiler waits for every LDS read
+        // issued so far (lgkmcnt(0)) in front of a unit's first MFMA whatever the reads are for,
+        // so the reads for the next unit are issued behind it and have the rest of the unit.
+        auto mfma_rows = [&](int i0, int i1) {
+#pragma unroll
+          for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+              acc[(u % UH) * AG + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                  af[u & 1][i], bf[(u / UH) & 1][j], acc[(u % UH) * AG + i][j], 0, 0, 0);
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_rows(0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (u + 1 < NU) {
+          read_a(sa, u + 1, af[(u + 1) & 1]);
+          if ((u + 1) % UH == 0) read_b(sb, (u + 1) / UH, bf[((u + 1) / UH) & 1]);
+          // this unit's share of what the barrier of the step before made room for
+          if (kt > 0) issue_some(kt - 1, sap, sbp, (u + 1) * NL / NU, (u + 2) * NL / NU);
+        } else if (kt + 1 < nkt) {
+          // this wavefront's loads up to B(kt+1) have landed (A(kt+2), the last LA loads it
+          // issued, may be in flight) and its fragment reads of step kt are complete (not merely
+          // issued: the loads that follow overwrite their slots)
+          if (kt + 2 < nkt) wait_vmcnt_lds<LA>(); else wait_vmcnt_lds<0>();
+          __builtin_amdgcn_s_barrier();
+          issue_some(kt, sa, sb, 0, NL / NU);
+          read_a(sa1, 0, af[0]);
+          read_b(sb1, 0, bf[0]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_rows(1, AG);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      sap = sa;
+      sbp = sb;
+      sa = sa1;
+    }
+  } else {
   DLLMC_LDS_ISSUE(0, rot)
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < nkt;
-    if (ONE_BARRIER) {
-      // this wavefront's loads of step kt have landed and its fragment reads of step kt-1 are
-      // complete (not merely issued: the loads below overwrite their stage)
-      wait_vmcnt_lds<0>();
-      __builtin_amdgcn_s_barrier();
-      if (more) DLLMC_LDS_ISSUE(cur ^ 1, kt + 1 + rot < nkt ? kt + 1 + rot : kt + 1 + rot - nkt)
-    } else {
+    {
       if (more) {
         DLLMC_LDS_ISSUE(cur ^ 1, kt + 1 + rot < nkt ? kt + 1 + rot : kt + 1 + rot - nkt)
         wait_vmcnt<LA + LB>();  // this wavefront's loads of step kt have landed
@@ -526,15 +678,14 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
     }
-    // two-barrier scheme: all fragment reads of this stage are complete before the loads issued
-    // at the top of the next iteration overwrite it.  The explicit wait matters: without it the
-    // compiler puts the wait for the last reads (and the MFMAs they feed) behind the barrier, and
-    // a load that hits in L1 (the neighbouring workgroup on the CU reads the same activation rows)
-    // can land before those reads execute.
-    if (!ONE_BARRIER) {
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-      __builtin_amdgcn_s_barrier();
-    }
+    // all fragment reads of this stage are complete before the loads issued at the top of the
+    // next iteration overwrite it.  The explicit wait matters: without it the compiler puts the
+    // wait for the last reads (and the MFMAs they feed) behind the barrier, and a load that hits
+    // in L1 (the neighbouring workgroup on the CU reads the same activation rows) can land
+    // before those reads execute.
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  }
   }
 #undef DLLMC_LDS_ISSUE
 
@@ -548,6 +699,15 @@ __device__ __forceinline__ void gemm_lds_body(const bf16_t* __restrict__ A, int 
     constexpr int kStg = 72;  // staging row stride in elements: 64 columns + 16 bytes
     static_assert(NWV * 16 * kStg * sizeof(bf16_t) <= kStage * sizeof(uint4), "staging fits a stage");
     __syncthreads();  // everybody has finished the fragment reads of the last step
+    if (ONE_BARRIER) {
+      static_assert(!ONE_BARRIER || NWV * 16 * kStg * sizeof(bf16_t) <= 4 * kSlot * sizeof(uint4),
+                    "staging stays clear of the table");
+      if (threadIdx.x < BM) {
+        meta[0][threadIdx.x] = meta_r0;
+        meta[1][threadIdx.x] = meta_r1;
+      }
+      __syncthreads();
+    }
     uint32_t* stg32 = reinterpret_cast<uint32_t*>(&lds[0][0]) + wave * (16 * kStg / 2);
     const bf16_t* stg = reinterpret_cast<const bf16_t*>(stg32);
     const int rr = lane / 8, ch = lane % 8;
