@@ -183,7 +183,7 @@ struct GemmTuning {
                        // fastest at both FFN widths (12288: one workgroup per CU)
   int force_s = 0;     // > 0: number of slices of the contraction index
   int target_wg = 256; // workgroups the automatic slice count aims for
-  int fat_min_m = 1024;     // activation rows from which the 256 x 256 LDS-direct kernel is used
+  int fat_min_m = 512;      // activation rows from which the 256 x 256 LDS-direct kernel is used
   int tall_max_m = 128;     // most rows the streaming kernel covers with one workgroup tile:
                             // 65..128 rows run with 128 rows per workgroup when it is >= 128
                             // (weights streamed once instead of once per 64-row tile); from
