@@ -19,6 +19,7 @@
 //                      gate/up column blocks and SwiGLU in the epilogue (k_gemm_*_swiglu,
 //                      k_gemm_tall_swiglu: 256 x 96 for up to 256 rows).
 #include <mutex>
+#include <type_traits>
 
 #include "common.hpp"
 
@@ -136,7 +137,9 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   constexpr int NWC = NW / KH;                    // wavefronts side by side over the columns
   static_assert(NW % KH == 0, "wavefront groups must be equal");
   __shared__ __attribute__((aligned(16))) bf16_t As[2][KH][R * LS];
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  // (the wavefront index as a scalar: the column block and whether the wavefront has one are
+  // then scalar too)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64), lane = threadIdx.x % 64;
   const int ln = lane % 16, lg = lane / 16;
   const int wcol = wave % NWC, kh = wave / NWC;
   int col_tile, row_tile;
@@ -163,6 +166,9 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
                                    : n_full * NWC + (col_tile - n_full) * (NWC - 1) + wcol;
   const bool active = (col_tile < n_full || wcol < NWC - 1) && cb * 16 < N;
   const int ncol = (active ? cb : 0) * 16 + ln;
+  // A wavefront without a block runs the same phases as the others (no branch in the loop: see
+  // below), on the first 256 contraction values of block 0 over and over: cache hits.
+  const int kmul = active ? 1 : 0;
   const bf16_t* wp[NB];
   if (DUAL) {
     wp[0] = W0 + static_cast<size_t>(ncol) * K + kbeg + kh * hlen + lg * 8;
@@ -207,50 +213,60 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
   uint4 a0[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) a0[j] = *reinterpret_cast<const uint4*>(asrc[j] + rot * KC);
-  // weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications
+  // Weight pieces in flight: one whole phase (KC / 128 steps) ahead of the multiplications, in
+  // two register sets that swap roles from phase to phase; a phase is straight-line code (the
+  // last one, which fetches nothing, is a variant of its own; a wavefront without a column block
+  // loads and multiplies like the others), and its barrier is a bare s_barrier behind a wait for
+  // the LDS operations only.  Each of these matters, because the wait counter counts loads in
+  // order and the compiler has to place its waits from what it can prove: (1) with one set,
+  // refilled piece by piece behind a copy of the piece being multiplied, it carries the set
+  // through the loop by copying the freshly loaded registers into place at the end of the body,
+  // and waits for every load of the phase to do so; (2) a __syncthreads() waits for every load in
+  // flight; (3) behind a join of paths that issued different numbers of loads (wavefronts
+  // without a block, the last phase) the activation chunks, the oldest loads of a phase, are
+  // waited for as if no younger load existed.  With any one of the three nothing stayed in
+  // flight across a phase boundary and a phase cost a full trip to memory (adaptive step of
+  // `llada8b` 5.45 -> 5.29 ms).  Three sets, two phases ahead, measured no better than two; nor
+  // did the first weight pieces issued ahead of the row list's wait (the activation chunks,
+  // which come from L2, then return behind them).
   constexpr int NS = KC / 128;
-  uint4 bn[NB][NS][4];
-  if (active) {
+  uint4 bset0[NB][NS][4], bset1[NB][NS][4];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+  for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int t = 0; t < NS; ++t)
+    for (int t = 0; t < NS; ++t)
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-          bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + rot * KC + t * 128 + c * 32);
-  }
+      for (int c = 0; c < 4; ++c)
+        bset0[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + (rot * KC + t * 128) * kmul + c * 32);
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     if (!aval[j]) a0[j] = make_uint4(0u, 0u, 0u, 0u);
     if (ain[j]) *reinterpret_cast<uint4*>(&As[0][0][adst[j]]) = a0[j];
   }
-  __syncthreads();
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wavefront's stores are complete
+  __builtin_amdgcn_s_barrier();
 
-  for (int ph = 0; ph < nph; ++ph) {
-    const bool more = ph + 1 < nph;
+  // one phase: multiply from `cur`; MORE: fetch the next phase's activation chunks and, as the
+  // steps go by, its weight pieces into `nxt`
+  auto phase = [&](auto more_tag, int ph, const uint4 (&cur)[NB][NS][4], uint4 (&nxt)[NB][NS][4]) {
+    constexpr bool MORE = decltype(more_tag)::value;
     int pn = ph + 1 + rot;  // the phase fetched during this one
     if (pn >= nph) pn -= nph;
     uint4 av[NCH];
-    if (more) {
+    if (MORE) {
 #pragma unroll
       for (int j = 0; j < NCH; ++j) av[j] = *reinterpret_cast<const uint4*>(asrc[j] + pn * KC);
     }
     const bf16_t* ap = &As[ph & 1][kh][ln * LS];
-    if (active) {
 #pragma unroll
     for (int t = 0; t < NS; ++t) {
-      uint4 bc[NB][4];
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) bc[b][c] = bn[b][t][c];
-      if (more) {
-        const int knext = pn * KC + t * 128;
+      if (MORE) {
+        const int knext = (pn * KC + t * 128) * kmul;
 #pragma unroll
         for (int b = 0; b < NB; ++b)
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            bn[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + knext + c * 32);
+            nxt[b][t][c] = *reinterpret_cast<const uint4*>(wp[b] + knext + c * 32);
       }
 #pragma unroll
       for (int c = 0; c < 4; ++c)
@@ -261,18 +277,34 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_stream(
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             acc[b][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                af, __builtin_bit_cast(bf16x8, bc[b][c]), acc[b][mb], 0, 0, 0);
+                af, __builtin_bit_cast(bf16x8, cur[b][t][c]), acc[b][mb], 0, 0, 0);
         }
     }
-    }
-    if (more) {
+    if (MORE) {
 #pragma unroll
       for (int j = 0; j < NCH; ++j) {
         if (!aval[j]) av[j] = make_uint4(0u, 0u, 0u, 0u);
         if (ain[j]) *reinterpret_cast<uint4*>(&As[(ph + 1) & 1][0][adst[j]]) = av[j];
       }
     }
-    __syncthreads();
+    // this wavefront's fragment reads of the phase and its stores for the next one are complete
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
+  {
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int ph = 0;
+    for (; ph + 2 < nph; ph += 2) {
+      phase(yes{}, ph, bset0, bset1);
+      phase(yes{}, ph + 1, bset1, bset0);
+    }
+    if (nph - ph == 2) {
+      phase(yes{}, ph, bset0, bset1);
+      phase(no{}, ph + 1, bset1, bset0);
+    } else if (nph - ph == 1) {
+      phase(no{}, ph, bset0, bset1);
+    }
   }
 
   if (KH > 1) {
@@ -1190,7 +1222,9 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
                         const void* w_gate, const void* w_up, int m, int K, void* u,
                         hipStream_t st) {
   if (M <= 0 || m <= 0) return true;
-  const int KC = (K % 256 == 0) ? 256 : 128;
+  // (phases of 128: the two register sets of gate and up pieces of a 256-wide phase do not fit
+  // beside the activation chunks)
+  const int KC = 128;
   // two wavefront groups over the two halves of K when the halves are whole phases
   const int KH = (g_tune.nw_dual >= 100 && K % (2 * KC) == 0) ? 2 : 1;
   int NW = g_tune.nw_dual % 100;  // wavefronts per workgroup
@@ -1268,12 +1302,12 @@ bool launch_gemm_swiglu(int dtype, const void* A, int lda, const int* rows, int 
     return true;
   }
   switch (NW * 10 + KH) {
-    case 62: if (KC == 256) DLLMC_GD(6, 256, 2); else DLLMC_GD(6, 128, 2); break;
-    case 82: if (KC == 256) DLLMC_GD(8, 256, 2); else DLLMC_GD(8, 128, 2); break;
-    case 31: if (KC == 256) DLLMC_GD(3, 256, 1); else DLLMC_GD(3, 128, 1); break;
-    case 81: if (KC == 256) DLLMC_GD(8, 256, 1); else DLLMC_GD(8, 128, 1); break;
-    case 42: if (KC == 256) DLLMC_GD(4, 256, 2); else DLLMC_GD(4, 128, 2); break;
-    default: if (KC == 256) DLLMC_GD(4, 256, 1); else DLLMC_GD(4, 128, 1); break;
+    case 62: DLLMC_GD(6, 128, 2); break;
+    case 82: DLLMC_GD(8, 128, 2); break;
+    case 31: DLLMC_GD(3, 128, 1); break;
+    case 81: DLLMC_GD(8, 128, 1); break;
+    case 42: DLLMC_GD(4, 128, 2); break;
+    default: DLLMC_GD(4, 128, 1); break;
   }
 #undef DLLMC_GD
   return true;
