@@ -12,7 +12,8 @@ OUT = os.path.join(HERE, "libdllmc.so")
 SOURCES = ("kernels_gemm.hip", "kernels_row.hip", "kernels_select.hip", "kernels_attn.hip", "kernels_gen.hip", "kernels_probe.hip", "kernels_fused.hip", "page_pool.cpp",
            "dllmc_api.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def build(verbose: bool = False) -> str:
