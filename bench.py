@@ -28,7 +28,7 @@ FP32_VALU_PEAK_TFLOPS = 157.3
 # figure comes from separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark,
 # scaled by the counters' reading for a 256 MiB copy (profiles/k_gemm_stream_<workload>_hbm_counters.txt);
 # None where no such run has been recorded for the workload.
-TRAFFIC_BYTES_PER_LAUNCH = {"llada8b": 113.7e6}
+TRAFFIC_BYTES_PER_LAUNCH = {"llada8b": 114.8e6}
 TRAFFIC_SOURCE = "profiles/k_gemm_stream_{name}_hbm_counters.txt (separate rocprofv3 --pmc runs, not this run)"
 
 
