@@ -122,7 +122,19 @@ def test_linear_fat_kernel(M, N, K):
     try:
         run_linear_case("bf16", M, N, K, True)
     finally:
-        binding.set_gemm_tuning(fat_min_m=1024)
+        binding.set_gemm_tuning(fat_min_m=512)
+
+
+@pytest.mark.parametrize("K", [128, 256, 384, 512, 768, 1024, 1280, 1536])
+@pytest.mark.parametrize("M,N", [(40, 128), (64, 256)])
+def test_linear_streaming_kernel_phase_counts(M, N, K):
+    """One slice, so that the workgroup walks K / 256 (or K / 128) phases: one to six, through the
+    paired loop and each of its tails."""
+    binding.set_gemm_tuning(force_s=1)
+    try:
+        run_linear_case("bf16", M, N, K, True)
+    finally:
+        binding.set_gemm_tuning(force_s=0)
 
 
 @pytest.mark.parametrize("nw", [8, 4])
