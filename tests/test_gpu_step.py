@@ -133,7 +133,7 @@ def test_fused_gate_up_in_tile_kernels(cfg, fat_min_m):
         PU.compare_caches(cfg, gpu, ora, st)
         gpu.close()
     finally:
-        binding.set_gemm_tuning(fat_min_m=1024)
+        binding.set_gemm_tuning(fat_min_m=512)
 
 
 def test_fused_gate_up_with_uneven_column_blocks():
