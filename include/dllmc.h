@@ -294,8 +294,8 @@ int dllmc_op_head(int32_t dtype, const void* hidden, const int32_t* rows, int32_
  * 48 columns of each matrix per workgroup); force_s number of contraction slices
  * (0 = automatic), target_wg
  * workgroups the automatic choice aims for, tile_min_m / fat_min_m number of activation rows
- * from which the 128 x 128 / the 256 x 256 LDS-direct tile kernel replaces the
- * weight-streaming kernel; tall_max_m (default 128; 0 = off): from 128 on, launches of 65..128
+ * (defaults 192 / 512) from which the 128 x 128 / the 256 x 256 LDS-direct tile kernel replaces
+ * the weight-streaming kernel; tall_max_m (default 128; 0 = off): from 128 on, launches of 65..128
  * rows run the weight-streaming kernel with 128 rows per workgroup (weights streamed once
  * instead of once per 64-row tile); from 256 on, launches of tile_min_m .. tall_max_m rows use
  * it with 256 rows per workgroup instead of the 128 x 128 tiles.
